@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the Dummy Forcing attention hot path on one MI355X.
+
+One "step" is one pass of the whole path over one chunk-layer of synthetic input that is
+already resident in HBM:
+
+    df_pack_context -> df_head_score (25% of the queries, all keys) -> df_attn_fwd (with the
+    fused frame attention score) -> df_kv_append, and, on the host, df_classify of the
+    scores copied back.
+
+Prints ONE JSON line.  `value` is algorithmic TFLOP/s of the step (attention + scoring FLOP
+over visible keys only, divided by the step time); `roofline` describes the dominant kernel
+(the attention kernel) from HIP-event timings taken inside the timed region; `cpu_baseline`
+is the fp64 oracle timed on this machine's host cores on a bounded row sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, datasheet
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, datasheet
+
+# HBM bytes per attention launch from rocprofv3 --pmc runs (FETCH_SIZE / WRITE_SIZE scaled by a
+# copy kernel of known size); see profiles/.  None = not measured for that workload yet.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def _blas_threads() -> int:
+    """Threads the oracle's numpy matmuls actually run on."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+        return max(n) if n else 1
+    except Exception:
+        return os.cpu_count() or 1
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config4", "config5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="oracle rows per head (0 = sized for ~15 s)")
+    return ap.parse_args()
+
+
+def build_state(w, df, torch, dev):
+    """Device-resident inputs plus a cache that already holds the workload's history."""
+    H, d = w.H, w.d
+    # cache capacities: what each head type keeps (heterogeneous allocation); dummy heads own no rows
+    sink_cap = [min(w.n_sink[h], w.Nh) for h in range(H)]
+    win_cap = [w.visible_len(h) - sink_cap[h] for h in range(H)]
+    rows = [s + x for s, x in zip(sink_cap, win_cap)]
+    row_off = [0]
+    for r in rows:
+        row_off.append(row_off[-1] + r)
+    k_cache = torch.empty(max(row_off[-1], 1), d, dtype=torch.bfloat16, device=dev)
+    v_cache = torch.empty(max(row_off[-1], 1), d, dtype=torch.bfloat16, device=dev)
+    cache = df.Cache(k_cache, v_cache, row_off, sink_cap, win_cap, d)
+    # fill the cache through the library itself: append the history frame by frame
+    kh, vh = w.k_hist.to(dev), w.v_hist.to(dev)
+    step = w.T * w.chunk_frames
+    for s in range(0, w.Nh, step):
+        df.df_kv_append(cache, kh[s:s + step], vh[s:s + step])
+    torch.cuda.synchronize()
+    # a second cache with the same state takes the appended chunk, so that every timed step
+    # packs the same pristine history (append overwrites the oldest window rows)
+    sink2 = torch.empty_like(k_cache), torch.empty_like(v_cache)
+    cache_b = df.Cache(sink2[0], sink2[1], row_off, sink_cap, win_cap, d)
+    for h in range(H):
+        cache_b.sink_len[h], cache_b.win_len[h], cache_b.win_pos[h] = cache.sink_len[h], cache.win_len[h], cache.win_pos[h]
+    st = dict(cache=cache, cache_b=cache_b, sink_cap=sink_cap, win_cap=win_cap,
+              q=w.q.to(dev), k_cur=w.k_cur.to(dev), v_cur=w.v_cur.to(dev),
+              k_pack=torch.empty(max(row_off[-1], 1), d, dtype=torch.bfloat16, device=dev),
+              v_pack=torch.empty(max(row_off[-1], 1), d, dtype=torch.bfloat16, device=dev),
+              out=torch.empty(w.Nq, H, d, dtype=torch.bfloat16, device=dev),
+              F_fused=torch.empty(H, 3, dtype=torch.float32, device=dev),
+              F_samp=torch.empty(H, 3, dtype=torch.float32, device=dev),
+              ws=torch.empty(df.df_attn_workspace_bytes(H, d, w.Nq), dtype=torch.uint8, device=dev),
+              ws2=torch.empty(df.df_attn_workspace_bytes(H, d, w.Nq), dtype=torch.uint8, device=dev))
+    del kh, vh
+    return st
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2601_20499_amd import binding as df
+    from paper_2601_20499_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    w = getattr(wl, args.workload)()
+    st = build_state(w, df, torch, dev)
+    H = w.H
+    n_dummy = sum(1 for t in w.head_type if t == wl.HEAD_DUMMY)
+    K, W = args.steps, args.warmup
+    F_host = [torch.empty(H, 3, dtype=torch.float32).pin_memory() for _ in range(K + W)]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    names = ["pack", "score", "attn", "append"]
+    marks = [[ev() for _ in range(5)] for _ in range(K + W)]
+    # df_kv_append mutates the cache; to time the same state every step the host arrays are restored
+    snap = (list(st["cache"].sink_len), list(st["cache"].win_len), list(st["cache"].win_pos))
+
+    def one_step(i):
+        c, cb = st["cache"], st["cache_b"]
+        for h in range(H):
+            cb.sink_len[h], cb.win_len[h], cb.win_pos[h] = snap[0][h], snap[1][h], snap[2][h]
+        m = marks[i]
+        m[0].record()
+        off, sl = df.df_pack_context(c, st["sink_cap"], st["win_cap"], st["k_pack"], st["v_pack"])
+        m[1].record()
+        df.df_head_score(st["q"], st["k_cur"], st["k_pack"], off, sl, st["F_samp"], w.scale,
+                         q_sample_stride=4, q_offset=0, workspace=st["ws2"])
+        F_host[i].copy_(st["F_samp"], non_blocking=True)
+        m[2].record()
+        df.df_attn_fwd(st["q"], st["k_cur"], st["v_cur"], st["k_pack"], st["v_pack"], off, sl, st["out"],
+                       w.scale, score_out=st["F_fused"], workspace=st["ws"])
+        m[3].record()
+        df.df_kv_append(cb, st["k_cur"], st["v_cur"])
+        m[4].record()
+
+    for i in range(W):
+        one_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(W, W + K):
+        one_step(i)
+    torch.cuda.synchronize()
+    types = None
+    for i in range(W, W + K):          # host part of the step: classification of the copied scores
+        types, _ = df.df_classify(F_host[i].tolist(), n_dummy, df.DF_CLASSIFY_TWO_CLASS)
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / K
+
+    per = {n: sum(marks[i][j].elapsed_time(marks[i][j + 1]) for i in range(W, W + K)) / K
+           for j, n in enumerate(names)}
+    attn_flop = w.attn_flop()
+    score_flop = sum(2.0 * ((w.Nq + 3) // 4) * (w.visible_len(h) + w.Nc) * w.d for h in range(H))
+    value = (attn_flop + score_flop) / (ms_step * 1e-3) / 1e12
+    attn_tflops = attn_flop / (per["attn"] * 1e-3) / 1e12
+    pack_bytes = 2 * 2 * sum(w.visible_len(h) for h in range(H)) * w.d * 2
+    kept = sum(1 for h in range(H) if st["sink_cap"][h] + st["win_cap"][h] > 0)
+    app_tokens = sum(min(w.Nc, st["win_cap"][h]) for h in range(H))
+    append_bytes = 2 * 2 * app_tokens * w.d * 2
+
+    result = {
+        "metric": "head-heterogeneous attention TFLOP/s + ms per chunk-layer; % bf16 MFMA peak",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "H": H, "d": w.d, "tokens_per_frame": w.T, "Nq": w.Nq,
+                   "keys_per_head": [w.visible_len(h) + w.Nc for h in range(H)],
+                   "dummy_heads": n_dummy, "step": "pack+head_score+attn(fused score)+append+classify",
+                   "classified_dummy": [h for h, t in enumerate(types) if t == df.DF_HEAD_DUMMY]},
+        "roofline": {"bound": "mfma", "kernel": "df_attn_kernel", "achieved": round(attn_tflops, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "flop_per_launch": attn_flop,
+                     "ms_per_launch": round(per["attn"], 4)},
+        "breakdown_ms": {k: round(v, 4) for k, v in per.items()},
+        "attn_ms_per_chunk_layer": round(per["attn"], 4),
+        "pack_GBps": round(pack_bytes / (per["pack"] * 1e-3) / 1e9, 1) if pack_bytes else None,
+        "append_GBps": round(append_bytes / (per["append"] * 1e-3) / 1e9, 1) if append_bytes else None,
+        "pack_frac_hbm": round(pack_bytes / (per["pack"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if pack_bytes else None,
+        "paper_context": "H100 end-to-end only: up to 2.0x speedup, 24.3 FPS, 17.6->19.6 FPS from pruning 25% of heads",
+    }
+
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from tests import gpu_util as gu  # row sampler and the oracle driver shared with the parity tests
+        n_rows = args.cpu_rows
+        if n_rows <= 0:
+            gu.oracle_rows(w, rows=np.arange(8))                       # warm the BLAS threads
+            t = time.perf_counter()
+            gu.oracle_rows(w, rows=np.arange(0, w.Nq, max(1, w.Nq // 64))[:64])
+            rate = 64 / max(time.perf_counter() - t, 1e-3)
+            n_rows = int(max(32, min(w.Nq, rate * 15)))
+        rows = np.linspace(0, w.Nq - 1, n_rows).astype(np.int64)
+        t = time.perf_counter()
+        ref, _, _ = gu.oracle_rows(w, rows=rows)
+        dt = time.perf_counter() - t
+        got = st["out"].float().cpu().double().numpy()[rows]
+        err = np.abs(got - ref)
+        flop = attn_flop * len(rows) / w.Nq
+        result["cpu_baseline"] = {"value": round(flop / dt / 1e12, 5), "unit": "TFLOP/s",
+                                  "cores": _blas_threads(), "kind": "oracle",
+                                  "sample": f"{len(rows)} of {w.Nq} query rows of every head, all visible keys, "
+                                            f"fp64 numpy, {dt:.1f} s",
+                                  "ms_per_chunk_layer_extrapolated": round(dt * 1e3 * w.Nq / len(rows), 1)}
+        result["parity_on_sample"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean())}
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

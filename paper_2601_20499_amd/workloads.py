@@ -121,6 +121,7 @@ def _draw(w: Workload, planted: List[int], bias: float = 2.0, weak_bias: Optiona
 
 
 def _typed(name, H, d, T, chunk_frames, hist_frames, types, seed, scale=None, sink_frames=1):
+    sink_frames = min(sink_frames, hist_frames)
     window_frames = hist_frames - sink_frames
     ctx = [_context(t, T, sink_frames, window_frames) for t in types]
     return Workload(name=name, H=H, d=d, T=T, chunk_frames=chunk_frames, hist_frames=hist_frames,

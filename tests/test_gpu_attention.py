@@ -1,0 +1,136 @@
+"""Parity of df_attn_fwd (through the C ABI) with the fp64 oracle on identical seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_20499_amd import workloads as wl
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def df():
+    from paper_2601_20499_amd import binding
+    return binding
+
+
+def _full_parity(df, w, layout="thd"):
+    out, score, lse = gu.run_attn(df, w, layout=layout)
+    ref, mass, rlse = gu.oracle_rows(w)
+    gu.check_out(out, ref, w.name)
+    F = mass.mean(axis=1)
+    assert np.abs(score - F).max() <= gu.F_ABS, (score, F)
+    assert np.abs(score.sum(1) - 1).max() <= 1e-5
+    assert np.abs(lse - rlse).max() <= gu.LSE_ABS
+    return out, score
+
+
+def test_config1_tiny(df):
+    w = wl.config1()
+    out, score = _full_parity(df, w)
+    assert out.shape == (64, 4, 64)
+    # the dummy head sees the current frame only: its score is exactly (0, 0, 1)
+    np.testing.assert_array_equal(score[3], [0.0, 0.0, 1.0])
+    # reported, not part of the bar: distance to the oracle run on the raw fp32 inputs
+    w32 = wl.config1(fp32=True)
+    ref32, _, _ = __import__("oracle.df_oracle", fromlist=["x"]).layer_attention(
+        w32.q.double().numpy(), [w32.k_hist[:, h].double().numpy() for h in range(4)],
+        [w32.v_hist[:, h].double().numpy() for h in range(4)], w32.k_cur.double().numpy(),
+        w32.v_cur.double().numpy(), w32.n_sink, w32.n_win, w32.scale)
+    print("config1 vs fp32-input oracle: max|err| = %.3e" % np.abs(out - ref32).max())
+
+
+@pytest.mark.parametrize("seed,H,d,T,hist_frames,types", [
+    (21, 3, 128, 97, 5, [wl.HEAD_FULL, wl.HEAD_DUMMY, wl.HEAD_NEIGHBOR]),       # 291 queries: ragged q tail, 8 key tiles
+    (22, 5, 128, 37, 4, [wl.HEAD_FULL, wl.HEAD_SINK, wl.HEAD_NEIGHBOR, wl.HEAD_DUMMY, wl.HEAD_PACK_DUMMY]),
+    (23, 4, 64, 50, 6, [wl.HEAD_SINK, wl.HEAD_PACK_DUMMY, wl.HEAD_FULL, wl.HEAD_DUMMY]),
+    (24, 2, 64, 129, 3, [wl.HEAD_NEIGHBOR, wl.HEAD_FULL]),
+    (25, 1, 128, 64, 2, [wl.HEAD_FULL]),                                         # everything a multiple of the tiles
+    (26, 2, 128, 1, 3, [wl.HEAD_FULL, wl.HEAD_DUMMY]),                           # one token per frame
+])
+def test_small_ragged_all_head_types(df, seed, H, d, T, hist_frames, types):
+    w = wl.small_ragged(seed, H=H, d=d, T=T, hist_frames=hist_frames, types=types, planted=[0])
+    _full_parity(df, w)
+
+
+def test_head_major_strides(df):
+    w = wl.small_ragged(27, H=3, d=128, T=70, hist_frames=3)
+    _full_parity(df, w, layout="htd")
+
+
+def test_no_history_first_step(df):
+    w = wl.small_ragged(28, H=3, d=128, T=45, hist_frames=0, types=[wl.HEAD_FULL, wl.HEAD_SINK, wl.HEAD_DUMMY])
+    assert w.Nh == 0
+    out, score = _full_parity(df, w)
+    np.testing.assert_array_equal(score, np.repeat([[0.0, 0.0, 1.0]], 3, 0))
+
+
+def test_structured_values_and_peaked_softmax(df):
+    """Cases where the absolute tolerance bites: values with an O(1) per-head mean, and logits
+    with a standard deviation of about 4 (a handful of keys carry each row)."""
+    w = wl.small_ragged(29, H=2, d=128, T=80, hist_frames=4, types=[wl.HEAD_FULL, wl.HEAD_FULL])
+    g = torch.Generator().manual_seed(5)
+    shift = torch.randn(2, 128, generator=g)
+    w.v_cur = (w.v_cur.float() + shift[None]).to(torch.bfloat16)
+    w.v_hist = (w.v_hist.float() + shift[None]).to(torch.bfloat16)
+    _full_parity(df, w)
+    w2 = wl.small_ragged(30, H=2, d=128, T=80, hist_frames=4, types=[wl.HEAD_FULL, wl.HEAD_NEIGHBOR], q_mean_std=0.0)
+    w2.scale = 4.0 / (128 ** 0.5)
+    _full_parity(df, w2)
+
+
+def test_bitwise_determinism_and_no_out_of_bounds_writes(df):
+    w = wl.small_ragged(31, H=3, d=128, T=97, hist_frames=5)
+    d = gu.dev()
+    kp, vp, off, sl = wl.packed_history(w)
+    q = w.q.to(d)
+    pad = 5
+    big = torch.full((w.Nq + 2 * pad, w.H, w.d), 7.0, dtype=torch.bfloat16, device=d)
+    outs = []
+    for _ in range(2):
+        big.fill_(7.0)
+        df.df_attn_fwd(q, w.k_cur.to(d), w.v_cur.to(d), kp.to(d), vp.to(d), off, sl, big[pad:pad + w.Nq], w.scale)
+        torch.cuda.synchronize()
+        outs.append(big.clone())
+    assert torch.equal(outs[0], outs[1])
+    assert (outs[0][:pad] == 7.0).all() and (outs[0][pad + w.Nq:] == 7.0).all()
+
+
+def _sampled_parity(df, w, n_rows, seed):
+    out, score, _ = gu.run_attn(df, w, want_lse=False)
+    rows = gu.sample_rows(w.Nq, n_rows, seed)
+    ref, mass, _ = gu.oracle_rows(w, rows=rows)
+    gu.check_out(out[rows], ref, w.name)
+    # properties that hold at any size
+    assert np.isfinite(out).all()
+    assert np.abs(score.sum(1) - 1).max() <= 1e-5
+    for h in range(w.H):
+        if w.visible_len(h) == 0:
+            np.testing.assert_array_equal(score[h], [0.0, 0.0, 1.0])
+    return out, score, rows, mass
+
+
+def test_config2_wan_shape_sampled_rows(df):
+    w = wl.config2()
+    assert w.attn_flop() == pytest.approx(336.4e9, rel=1e-3)
+    out, score, rows, mass = _sampled_parity(df, w, 192, seed=2)
+    # the recipe's bands: planted heads concentrate on the current chunk, the others split by key count
+    F_rows = mass.mean(axis=1)
+    for h in range(w.H):
+        if h in w.planted:
+            continue
+        np.testing.assert_allclose(F_rows[h], [1 / 9, 5 / 9, 3 / 9], atol=0.03)
+        assert np.abs(score[h] - F_rows[h]).max() < 0.02      # all rows vs the row sample
+
+
+def test_config4_720p_sampled_rows(df):
+    w = wl.config4()
+    _sampled_parity(df, w, 96, seed=4)
+
+
+def test_config5_long_context_sampled_rows(df):
+    w = wl.config5()
+    lens = sorted(w.visible_len(h) for h in range(w.H))
+    assert lens[0] == 0 and lens[6] == 4680 and lens[-1] == 93600
+    _sampled_parity(df, w, 64, seed=5)
