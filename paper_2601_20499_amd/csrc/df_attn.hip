@@ -1,24 +1,40 @@
 // df_attn_fwd / df_head_score: varlen-per-head flash-style attention for gfx950.
 //
-// One workgroup (4 wavefronts of 64 lanes) owns one (head, query tile) unit and
-// streams that head's visible keys - sink region, window region, current chunk,
-// in this order (the concatenation order of Eq. 2) - through LDS in tiles of 64
-// keys.  A dummy head has an empty history, so its units iterate the current
-// chunk only: no masked tile is ever issued.  Units are launched longest head
-// first so that the hardware dispatcher back-fills short (dummy) units.
+// Work decomposition.  One workgroup of 8 wavefronts owns one (head, 256-query
+// tile) unit; each wavefront owns 32 queries and streams the head's visible
+// keys - sink region, window region, current chunk, in this order (the
+// concatenation order of Eq. 2) - in tiles of 64 keys.  A dummy head has an
+// empty history, so its units iterate the current chunk only: no masked tile
+// is ever issued.  Units are ordered longest head first and laid out so that
+// the workgroups of one XCD (workgroup id mod 8) work on neighbouring query
+// tiles of the same head and share its K/V tiles in that XCD's L2.
 //
-// Per wavefront the scores are computed transposed, S^T = K Q^T, with
-// v_mfma_f32_32x32x16_bf16: the K tile is the A operand (read from LDS), the
-// wave's Q fragment is the B operand (held in registers for the whole unit).
-// In the 32x32 accumulator layout each lane then owns ONE query (column
-// lane%32) and 16 of the 32 keys of a block, so the softmax row reductions are
-// in-lane except for one exchange with lane^32, and the probabilities are
-// already in the register layout the second product needs as its B operand:
-// O^T += V^T P^T, with V^T tiles read from LDS as the A operand.
+// MFMA mapping.  Scores are computed transposed, S^T = K Q^T, with
+// v_mfma_f32_32x32x16_bf16: the K tile is the A operand (ds_read_b128 from a
+// row-major LDS tile), the wave's Q fragment is the B operand (registers, loaded
+// once per unit).  In the 32x32 accumulator layout a lane owns ONE query
+// (column lane%32) and 16 of the 32 keys of a block, so the softmax row
+// reductions are in-lane except for one exchange with lane^32, and the
+// probabilities are already in the register layout the second product needs
+// as its B operand: O^T += V^T P^T.  V^T is the A operand and is read from a
+// row-major V tile in LDS with the transposing ds_read_b64_tr_b16.
 //
-// Online softmax keeps a running row maximum m and per-lane partial row sums l
-// in fp32; P is rounded to bf16 (RNE) before the second product; the output is
-// divided by l and rounded to bf16 once at the end.
+// Schedule.  The 8 waves form two groups of 4 (one wave of each group per
+// SIMD).  Every tile iteration of a wave has an MFMA phase (S = K Q^T of tile t
+// and O += V^T P^T of tile t-1) and a VALU/memory phase (online softmax of tile
+// t, LDS stores of the staged tile, global loads of a later tile), separated
+// by workgroup barriers.  Group 1 starts one barrier late, so on every SIMD one
+// wave is in its MFMA phase while the other is in its VALU phase: the matrix
+// core and the vector ALU overlap without relying on instruction scheduling.
+// K and V tiles rotate through three LDS buffers each; with the one-phase
+// stagger a buffer is rewritten only after both groups have finished reading it.
+//
+// Online softmax keeps a running row maximum m and per-lane partial row sums
+// l in fp32.  The maximum is only raised (and O, l rescaled) when some row of
+// the wave exceeds it by more than 2^8, which keeps P within bf16/fp32 range
+// and makes rescaling rare; P is rounded to bf16 (RNE) before the second
+// product; l sums the fp32 values.  The output is divided by l and
+// rounded to bf16 once at the end.
 //
 // The frame attention score of Eq. 3 falls out of the same statistics: with the
 // keys ordered sink | window | current, snapshots (m1,l1) after the sink region
@@ -33,16 +49,20 @@
 namespace df {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16;
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
-constexpr int kKT = 64;      // keys per LDS tile
-constexpr int kPad = 8;      // bf16 elements of row padding in LDS (16 bytes)
+constexpr int kThreads = 512;
+constexpr int kWaves = 8;
+constexpr int kBQ = kWaves * 32;   // queries per workgroup
+constexpr int kKT = 64;            // keys per LDS tile
+constexpr int kNBuf = 3;           // LDS buffers per operand
+constexpr float kRescaleLog2 = 8.f;  // raise the running maximum only beyond this many powers of two
+constexpr int kXcd = 8;            // XCDs per device: consecutive workgroup ids go to consecutive XCDs
 
 struct AttnParams {
   const u16 *q, *k_cur, *v_cur, *k_hist, *v_hist;
@@ -50,7 +70,7 @@ struct AttnParams {
   float *lse;          // [H, Nq] or null
   float *part;         // workspace: [H, n_qtiles, 4] partial score sums, or null
   int64_t q_st, q_sh, kc_st, kc_sh, o_st, o_sh;
-  int32_t Nq, Nc, H, n_qtiles;
+  int32_t Nq, Nc, H, n_qtiles, n_units, units_per_xcd;
   float c;             // softmax_scale * log2(e)
   float scale;         // softmax_scale
   int64_t hist_off[kMaxHeads + 1];
@@ -66,6 +86,21 @@ __device__ __forceinline__ unsigned pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(unsigned, h);
 }
 
+// Both values of the lane pair (lane, lane^32): a = the lower lane's value, b = the upper lane's.
+// v_permlane32_swap_b32 exchanges lanes 32..63 of its first operand with lanes 0..31 of its second.
+__device__ __forceinline__ void pair_values(float x, float &a, float &b) {
+  a = x;
+  b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float pair_max(float x) { float a, b; pair_values(x, a, b); return fmaxf(a, b); }
+__device__ __forceinline__ float pair_sum(float x) { float a, b; pair_values(x, a, b); return a + b; }
+
+// Workgroup barrier that waits for this wave's LDS traffic only: global loads stay in flight.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Position, inside a 32-key block, of the key whose scores land in accumulator
 // row i: bits 2 and 3 of i are exchanged.  With it, accumulator registers
 // 8t..8t+7 of a lane in half hf hold the 8 consecutive keys 16t+8hf .. +7,
@@ -74,230 +109,270 @@ __device__ __forceinline__ int key_of_row(int i) {
   return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
 }
 
-template <int D, int QB, bool SCORE_ONLY>
-__global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
-  constexpr int BQ = kWaves * 32 * QB;
-  constexpr int KS = D / 16;           // k-steps of the first product
-  constexpr int DB = D / 32;           // 32-row blocks of O^T
-  constexpr int KROW = D + kPad;       // LDS row length of the K tile   [kKT][KROW]
-  constexpr int VROW = kKT + kPad;     // LDS row length of the V^T tile [D][VROW]
-  __shared__ __attribute__((aligned(16))) u16 lds_k[kKT * KROW];
-  __shared__ __attribute__((aligned(16))) u16 lds_vt[SCORE_ONLY ? 8 : D * VROW];
-  __shared__ float lds_red[BQ * 2];
+// One key tile of a head: where its rows live and how many of the 64 are real.
+struct Tile {
+  const u16 *k, *v;
+  int64_t stride;
+  int n_valid;
+};
 
-  const int unit = blockIdx.x;
-  const int h = p.order[unit / p.n_qtiles];
-  const int qt = unit % p.n_qtiles;
+template <int D, bool SCORE_ONLY>
+__global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
+  constexpr int KS = D / 16;            // k-steps of the first product
+  constexpr int DB = D / 32;            // 32-row blocks of O^T
+  constexpr int KROW = D + 8;           // K tile row, +16 B: conflict-free ds_read_b128 of 32 rows
+  constexpr int VROW = D + 32;          // V tile row, +64 B: conflict-free ds_read_b64_tr_b16
+  constexpr int KTILE = kKT * KROW, VTILE = kKT * VROW;
+  constexpr int VEC_PER_ROW = D / 8;    // 16-byte vectors per row
+  constexpr int ROWS_PER_PASS = kThreads / VEC_PER_ROW;
+  constexpr int NPASS = kKT / ROWS_PER_PASS;   // 2 for D=128, 1 for D=64
+  __shared__ __attribute__((aligned(16))) u16 lds_k[kNBuf * KTILE];
+  __shared__ __attribute__((aligned(16))) u16 lds_v[SCORE_ONLY ? 8 : kNBuf * VTILE];
+  __shared__ float lds_red[kBQ * 2];
+
+  // ---- which unit: XCD x (= workgroup id mod 8) takes logical units [x*upx, (x+1)*upx)
+  const int logical = (blockIdx.x % kXcd) * p.units_per_xcd + blockIdx.x / kXcd;
+  if (logical >= p.n_units) return;
+  const int h = p.order[logical / p.n_qtiles];
+  const int qt = logical % p.n_qtiles;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
+  const int group = wave >> 2;
   const int j = lane & 31, hf = lane >> 5;
-  const int q0 = qt * BQ + wave * 32 * QB;
+  const int q0 = qt * kBQ + wave * 32;
 
-  // ---- Q fragment: B operand of S^T = K Q^T.  Lane (j, hf) holds, for query j of each
-  // 32-query block, elements 16*ks + 8*hf .. +7 of every k-step.
-  bf16x8 qf[QB][KS];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    int row = q0 + 32 * qb + j;
-    row = row < p.Nq ? row : p.Nq - 1;           // tail rows re-read the last query; never stored
-    const u16 *src = p.q + row * p.q_st + h * p.q_sh + 8 * hf;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-      qf[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
-  }
-
-  f32x16 o[DB][QB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[db][qb][v] = 0.f;
-  float m[QB], l[QB], snap_m[2][QB], snap_l[2][QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) { m[qb] = -INFINITY; l[qb] = 0.f; }
-
+  // ---- tiles of this head: three segments, each cut into 64-key tiles
   const int64_t hoff = p.hist_off[h];
   const int len_h = int(p.hist_off[h + 1] - hoff);
   const int sink = p.sink_len[h];
+  const int nt0 = (sink + kKT - 1) / kKT;
+  const int nt1 = (len_h - sink + kKT - 1) / kKT;
+  const int nt2 = (p.Nc + kKT - 1) / kKT;
+  const int n_tiles = nt0 + nt1 + nt2;
+  auto tile_at = [&](int t) -> Tile {
+    Tile r;
+    if (t < nt0) {
+      const int k0 = t * kKT;
+      r.k = p.k_hist + (hoff + k0) * D; r.v = p.v_hist + (hoff + k0) * D; r.stride = D; r.n_valid = min(kKT, sink - k0);
+    } else if (t < nt0 + nt1) {
+      const int k0 = (t - nt0) * kKT;
+      r.k = p.k_hist + (hoff + sink + k0) * D; r.v = p.v_hist + (hoff + sink + k0) * D; r.stride = D;
+      r.n_valid = min(kKT, len_h - sink - k0);
+    } else {
+      const int k0 = (t - nt0 - nt1) * kKT;
+      r.k = p.k_cur + h * p.kc_sh + k0 * p.kc_st; r.v = p.v_cur + h * p.kc_sh + k0 * p.kc_st; r.stride = p.kc_st;
+      r.n_valid = min(kKT, p.Nc - k0);
+    }
+    return r;
+  };
+
+  // ---- global -> register -> LDS staging of one tile (rows past n_valid are zero-filled)
+  const int st_col = tid % VEC_PER_ROW, st_row = tid / VEC_PER_ROW;
+  auto load_tile = [&](const u16 *base, int64_t stride, int n_valid, u32x4 (&reg)[NPASS]) {
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+      const int r = st_row + i * ROWS_PER_PASS;
+      u32x4 z = {0u, 0u, 0u, 0u};
+      reg[i] = z;
+      if (r < n_valid) reg[i] = *reinterpret_cast<const u32x4 *>(base + r * stride + 8 * st_col);
+    }
+  };
+  auto store_tile = [&](u16 *lds, int row_len, const u32x4 (&reg)[NPASS]) {
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+      const int r = st_row + i * ROWS_PER_PASS;
+      *reinterpret_cast<u32x4 *>(lds + r * row_len + 8 * st_col) = reg[i];
+    }
+  };
+
+  // ---- Q fragment: B operand of S^T = K Q^T.  Lane (j, hf) holds, for query j,
+  // elements 16*ks + 8*hf .. +7 of every k-step.
+  bf16x8 qf[KS];
+  {
+    int row = q0 + j;
+    row = row < p.Nq ? row : p.Nq - 1;          // tail rows re-read the last query; never stored
+    const u16 *src = p.q + row * p.q_st + h * p.q_sh + 8 * hf;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+  }
+
+  // ---- prologue: K(0), V(0), K(1) into LDS; K(2) and V(1) staged in registers
+  u32x4 kreg[NPASS], vreg[NPASS];
+  {
+    Tile t0 = tile_at(0);
+    load_tile(t0.k, t0.stride, t0.n_valid, kreg);
+    store_tile(lds_k, KROW, kreg);
+    if (!SCORE_ONLY) {
+      load_tile(t0.v, t0.stride, t0.n_valid, vreg);
+      store_tile(lds_v, VROW, vreg);
+    }
+    if (n_tiles > 1) {
+      Tile t1 = tile_at(1);
+      load_tile(t1.k, t1.stride, t1.n_valid, kreg);
+      store_tile(lds_k + KTILE, KROW, kreg);
+      if (!SCORE_ONLY) load_tile(t1.v, t1.stride, t1.n_valid, vreg);
+    }
+    if (n_tiles > 2) {
+      Tile t2 = tile_at(2);
+      load_tile(t2.k, t2.stride, t2.n_valid, kreg);
+    }
+  }
+  lds_barrier();
+  if (group == 1) lds_barrier();          // stagger: group 1 runs one phase behind group 0
+
+  f32x16 o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+  float m = -INFINITY, l = 0.f;
+  float snap_m0 = -INFINITY, snap_l0 = 0.f, snap_m1 = -INFINITY, snap_l1 = 0.f;
+  f32x16 s[2];
+  bf16x8 pb[2][2];                         // P^T of the previous tile, [key block][16-key step]
+
+  // per-lane LDS offsets (elements) of the MFMA A operands
+  const int a_k = key_of_row(j) * KROW + 8 * hf;
+  const int g16 = lane >> 4, i16 = lane & 15;
+  const int a_v = (8 * (g16 >> 1) + (i16 >> 2)) * VROW + 16 * (g16 & 1) + 4 * (i16 & 3);
 
 #pragma unroll 1
-  for (int seg = 0; seg < 3; ++seg) {
-    // segment = (base pointers, row stride, number of keys)
-    const u16 *kbase, *vbase;
-    int64_t rstride;
-    int n_keys;
-    if (seg == 0)      { kbase = p.k_hist + hoff * D;          vbase = p.v_hist + hoff * D;          rstride = D; n_keys = sink; }
-    else if (seg == 1) { kbase = p.k_hist + (hoff + sink) * D; vbase = p.v_hist + (hoff + sink) * D; rstride = D; n_keys = len_h - sink; }
-    else               { kbase = p.k_cur + h * p.kc_sh;        vbase = p.v_cur + h * p.kc_sh;        rstride = p.kc_st; n_keys = p.Nc; }
-
-#pragma unroll 1
-    for (int k0 = 0; k0 < n_keys; k0 += kKT) {
-      const int n_valid = min(kKT, n_keys - k0);
-      __syncthreads();                             // previous tile fully consumed
-      // ---- stage the K tile (row-major) and the V tile (transposed) in LDS
-      {
-        constexpr int VEC_PER_ROW = D / 8;
-        constexpr int ROWS_PER_PASS = kThreads / VEC_PER_ROW;
-        const int cv = tid % VEC_PER_ROW, r0 = tid / VEC_PER_ROW;
-#pragma unroll
-        for (int r = r0; r < kKT; r += ROWS_PER_PASS) {
-          uint4 kv = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-          if (r < n_valid) {
-            kv = *reinterpret_cast<const uint4 *>(kbase + (k0 + r) * rstride + 8 * cv);
-            if (!SCORE_ONLY) vv = *reinterpret_cast<const uint4 *>(vbase + (k0 + r) * rstride + 8 * cv);
-          }
-          *reinterpret_cast<uint4 *>(&lds_k[r * KROW + 8 * cv]) = kv;
-          if (!SCORE_ONLY) {
-            const unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              lds_vt[(8 * cv + 2 * e) * VROW + r] = u16(w[e] & 0xffffu);
-              lds_vt[(8 * cv + 2 * e + 1) * VROW + r] = u16(w[e] >> 16);
-            }
-          }
-        }
-      }
-      __syncthreads();
-
-      // ---- S^T = K Q^T for 2 key blocks x QB query blocks
-      f32x16 s[2][QB];
+  for (int t = 0; t <= n_tiles; ++t) {
+    // ================= MFMA phase =================
+    if (t < n_tiles) {
+      const u16 *kt = lds_k + (t % kNBuf) * KTILE + a_k;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
+        for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) s[kb][qb][v] = 0.f;
+      for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const u16 *arow = &lds_k[(32 * kb + key_of_row(j)) * KROW + 8 * hf];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8 *>(arow + 16 * ks);
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-            s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[kb][qb], 0, 0, 0);
+        for (int kb = 0; kb < 2; ++kb) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kt + 32 * kb * KROW + 16 * ks);
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
         }
-      }
-      // ---- mask the keys past the end of the segment (last tile only)
-      if (n_valid < kKT) {
+    }
+    if (!SCORE_ONLY && t > 0) {
+      const u16 *vt = lds_v + ((t - 1) % kNBuf) * VTILE + a_v;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+          for (int db = 0; db < DB; ++db) {
+            const u16 *src = vt + (32 * kb + 16 * ts) * VROW + 32 * db;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4 __attribute__((address_space(3))) *)(src));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4 __attribute__((address_space(3))) *)(src + 4 * VROW));
+            const short a8 __attribute__((ext_vector_type(8))) = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb[kb][ts], o[db], 0, 0, 0);
+          }
+    }
+    lds_barrier();
+    // ================= VALU / memory phase =================
+    // staged tiles K(t+2), V(t+1) -> LDS; then fetch K(t+3), V(t+2)
+    if (t + 2 < n_tiles) store_tile(lds_k + ((t + 2) % kNBuf) * KTILE, KROW, kreg);
+    if (!SCORE_ONLY && t + 1 < n_tiles) store_tile(lds_v + ((t + 1) % kNBuf) * VTILE, VROW, vreg);
+    if (t + 3 < n_tiles) {
+      Tile nx = tile_at(t + 3);
+      load_tile(nx.k, nx.stride, nx.n_valid, kreg);
+    }
+    if (!SCORE_ONLY && t + 2 < n_tiles) {
+      Tile nx = tile_at(t + 2);
+      load_tile(nx.v, nx.stride, nx.n_valid, vreg);
+    }
+    if (t < n_tiles) {
+      const int seg_end0 = nt0 - 1, seg_end1 = nt0 + nt1 - 1;
+      int n_valid = kKT;
+      if (t == seg_end0) n_valid = sink - (nt0 - 1) * kKT;
+      else if (t == seg_end1) n_valid = len_h - sink - (nt1 - 1) * kKT;
+      else if (t == n_tiles - 1) n_valid = p.Nc - (nt2 - 1) * kKT;
+      if (n_valid < kKT) {                  // keys past the end of the segment
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int key = 32 * kb + 16 * (v >> 3) + 8 * hf + (v & 7);
-            if (key >= n_valid) {
-#pragma unroll
-              for (int qb = 0; qb < QB; ++qb) s[kb][qb][v] = -INFINITY;
-            }
+            if (key >= n_valid) s[kb][v] = -INFINITY;
           }
       }
-      // ---- online softmax, one query per lane pair (lane, lane^32)
+      float mx = s[0][0];
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        float mx = s[0][qb][0];
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][qb][v]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m[qb], mx);
-        const float alpha = fast_exp2((m[qb] - m_new) * p.c);
-        const float nmc = -m_new * p.c;
-        m[qb] = m_new;
-        float rs = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float e = fast_exp2(__builtin_fmaf(s[kb][qb][v], p.c, nmc));
-            s[kb][qb][v] = e;
-            rs += e;
-          }
-        l[qb] = l[qb] * alpha + rs;
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
+      mx = pair_max(mx);
+      // raise the running maximum only when some row of the wave outgrew it by 2^kRescaleLog2
+      if (__any((mx - m) * p.c > kRescaleLog2)) {
+        const float m_new = fmaxf(m, mx);
+        const float alpha = fast_exp2((m - m_new) * p.c);
+        m = m_new;
+        l *= alpha;
         if (!SCORE_ONLY) {
 #pragma unroll
           for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][qb][v] *= alpha;
+            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
         }
       }
-      // ---- O^T += V^T P^T
-      if (!SCORE_ONLY) {
+      const float nmc = -m * p.c;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            bf16x8 pb[QB];
+        for (int ts = 0; ts < 2; ++ts) {
+          unsigned w[4];
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-              unsigned w[4];
-#pragma unroll
-              for (int e = 0; e < 4; ++e)
-                w[e] = pack_bf16x2(s[kb][qb][8 * t + 2 * e], s[kb][qb][8 * t + 2 * e + 1]);
-              uint4 u = {w[0], w[1], w[2], w[3]};
-              pb[qb] = __builtin_bit_cast(bf16x8, u);
-            }
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-              const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
-                  &lds_vt[(32 * db + j) * VROW + 32 * kb + 16 * t + 8 * hf]);
-#pragma unroll
-              for (int qb = 0; qb < QB; ++qb)
-                o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb], o[db][qb], 0, 0, 0);
-            }
+          for (int e = 0; e < 4; ++e) {
+            const float e0 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e], p.c, nmc));
+            const float e1 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e + 1], p.c, nmc));
+            w[e] = pack_bf16x2(e0, e1);
+            l += e0 + e1;
           }
-      }
+          u32x4 u = {w[0], w[1], w[2], w[3]};
+          pb[kb][ts] = __builtin_bit_cast(bf16x8, u);
+        }
+      if (t == seg_end0) { snap_m0 = m; snap_l0 = l; }
+      if (t == seg_end1) { snap_m1 = m; snap_l1 = l; }
     }
-    if (seg < 2) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) { snap_m[seg][qb] = m[qb]; snap_l[seg][qb] = l[qb]; }
-    }
+    lds_barrier();
   }
+  if (group == 0) lds_barrier();          // matches group 1's extra barrier at the start
+  if (nt0 == 0) { snap_m0 = -INFINITY; snap_l0 = 0.f; }
+  if (nt1 == 0) { snap_m1 = snap_m0; snap_l1 = snap_l0; }
 
   // ---- epilogue: normalise, store, optional lse and score partials
-  float mass_a[QB], mass_b[QB];     // row mass on sink, on sink+window
+  const float lt = pair_sum(l);
+  const float inv = 1.f / lt;
+  const int row = q0 + j;
+  const bool valid = row < p.Nq;
+  const float l1 = pair_sum(snap_l0 * fast_exp2((snap_m0 - m) * p.c));
+  const float l2 = pair_sum(snap_l1 * fast_exp2((snap_m1 - m) * p.c));
+  const float mass_a = valid ? l1 * inv : 0.f;     // row mass on the sink region
+  const float mass_b = valid ? l2 * inv : 0.f;     // row mass on sink + window
+  if (!SCORE_ONLY && valid) {
+    u16 *dst = p.out + row * p.o_st + h * p.o_sh + 4 * hf;
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const float lt = l[qb] + __shfl_xor(l[qb], 32, 64);
-    const float inv = 1.f / lt;
-    const int row = q0 + 32 * qb + j;
-    const bool valid = row < p.Nq;
-    float l1 = snap_l[0][qb] * fast_exp2((snap_m[0][qb] - m[qb]) * p.c);
-    float l2 = snap_l[1][qb] * fast_exp2((snap_m[1][qb] - m[qb]) * p.c);
-    l1 += __shfl_xor(l1, 32, 64);
-    l2 += __shfl_xor(l2, 32, 64);
-    mass_a[qb] = valid ? l1 * inv : 0.f;
-    mass_b[qb] = valid ? l2 * inv : 0.f;
-    if (!SCORE_ONLY && valid) {
-      u16 *dst = p.out + row * p.o_st + h * p.o_sh + 4 * hf;
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int cq = 0; cq < 4; ++cq) {
-          uint2 w;
-          w.x = pack_bf16x2(o[db][qb][4 * cq] * inv, o[db][qb][4 * cq + 1] * inv);
-          w.y = pack_bf16x2(o[db][qb][4 * cq + 2] * inv, o[db][qb][4 * cq + 3] * inv);
-          *reinterpret_cast<uint2 *>(dst + 32 * db + 8 * cq) = w;
-        }
-      if (p.lse != nullptr && hf == 0)
-        p.lse[int64_t(h) * p.Nq + row] = m[qb] * p.scale + __logf(lt);
-    }
+      for (int cq = 0; cq < 4; ++cq) {
+        uint2 w;
+        w.x = pack_bf16x2(o[db][4 * cq] * inv, o[db][4 * cq + 1] * inv);
+        w.y = pack_bf16x2(o[db][4 * cq + 2] * inv, o[db][4 * cq + 3] * inv);
+        *reinterpret_cast<uint2 *>(dst + 32 * db + 8 * cq) = w;
+      }
+    if (p.lse != nullptr && hf == 0) p.lse[int64_t(h) * p.Nq + row] = m * p.scale + __logf(lt);
   }
   if (p.part != nullptr) {
     // deterministic block reduction: one slot per query, summed in index order by two threads
     if (hf == 0) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int qi = wave * 32 * QB + 32 * qb + j;
-        lds_red[2 * qi] = mass_a[qb];
-        lds_red[2 * qi + 1] = mass_b[qb];
-      }
+      lds_red[2 * (wave * 32 + j)] = mass_a;
+      lds_red[2 * (wave * 32 + j) + 1] = mass_b;
     }
     __syncthreads();
     if (tid < 2) {
       float acc = 0.f;
-      for (int qi = 0; qi < BQ; ++qi) acc += lds_red[2 * qi + tid];
+      for (int qi = 0; qi < kBQ; ++qi) acc += lds_red[2 * qi + tid];
       p.part[(int64_t(h) * p.n_qtiles + qt) * 4 + tid] = acc;
     }
   }
@@ -325,12 +400,13 @@ static size_t workspace_bytes(int H, int Nq) {
   return ((size_t(H) * tiles * 4 * sizeof(float) + 255) / 256) * 256 + 256;
 }
 
-template <int D, int QB, bool SCORE_ONLY>
+template <int D, bool SCORE_ONLY>
 static df_status launch(AttnParams &p, float *score_out, hipStream_t st) {
-  constexpr int BQ = kWaves * 32 * QB;
-  p.n_qtiles = (p.Nq + BQ - 1) / BQ;
-  dim3 grid(p.n_qtiles * p.H);
-  hipLaunchKernelGGL((df_attn_kernel<D, QB, SCORE_ONLY>), grid, dim3(kThreads), 0, st, p);
+  p.n_qtiles = (p.Nq + kBQ - 1) / kBQ;
+  p.n_units = p.n_qtiles * p.H;
+  p.units_per_xcd = (p.n_units + kXcd - 1) / kXcd;
+  dim3 grid(p.units_per_xcd * kXcd);
+  hipLaunchKernelGGL((df_attn_kernel<D, SCORE_ONLY>), grid, dim3(kThreads), 0, st, p);
   if (df_status s = launch_status()) return s;
   if (score_out) {
     hipLaunchKernelGGL(df_score_finish_kernel, dim3(p.H), dim3(64), 0, st, p.part, score_out, p.n_qtiles, p.Nq);
@@ -416,8 +492,8 @@ extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
   p.scale = a->softmax_scale;
   p.c = a->softmax_scale * 1.4426950408889634f;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (a->d == 128) return launch<128, 1, false>(p, a->score_out, st);
-  return launch<64, 1, false>(p, a->score_out, st);
+  if (a->d == 128) return launch<128, false>(p, a->score_out, st);
+  return launch<64, false>(p, a->score_out, st);
 }
 
 extern "C" df_status df_head_score(const df_score_args *a, void *stream) {
@@ -454,6 +530,6 @@ extern "C" df_status df_head_score(const df_score_args *a, void *stream) {
   p.scale = a->softmax_scale;
   p.c = a->softmax_scale * 1.4426950408889634f;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (a->d == 128) return launch<128, 1, true>(p, a->score_out, st);
-  return launch<64, 1, true>(p, a->score_out, st);
+  if (a->d == 128) return launch<128, true>(p, a->score_out, st);
+  return launch<64, true>(p, a->score_out, st);
 }
