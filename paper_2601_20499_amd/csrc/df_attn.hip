@@ -26,14 +26,23 @@
 // by workgroup barriers.  Group 1 starts one barrier late, so on every SIMD one
 // wave is in its MFMA phase while the other is in its VALU phase: the matrix
 // core and the vector ALU overlap without relying on instruction scheduling.
-// K and V tiles rotate through three LDS buffers each; with the one-phase
-// stagger a buffer is rewritten only after both groups have finished reading it.
+//
+// Staging.  K and V tiles go from global memory straight into LDS with
+// buffer_load_dwordx4 ... lds (no registers, no LDS store instructions); rows
+// past the end of a head's buffer read as zero through the buffer range check.
+// One such instruction fills 1 KB of LDS contiguously, so a tile is stored as
+// groups of rows {g, g+NG, g+2NG, ...} (NG = 16 groups for d = 128), each group
+// 1 KB plus a small pad.  With 16 B of pad per K group the 32 rows a wavefront
+// reads per ds_read_b128 fall into distinct banks, with 64 B per V group the
+// four consecutive keys of a ds_read_b64_tr_b16 do, and every operand address
+// is still "lane base + compile-time offset".  Tiles rotate through four LDS
+// buffers each; loads are issued three phases before their first use.
 //
 // Online softmax keeps a running row maximum m and per-lane partial row sums
 // l in fp32.  The maximum is only raised (and O, l rescaled) when some row of
 // the wave exceeds it by more than 2^8, which keeps P within bf16/fp32 range
 // and makes rescaling rare; P is rounded to bf16 (RNE) before the second
-// product; l sums the fp32 values.  The output is divided by l and
+// product and l sums the rounded values (v_dot2 with ones).  The output is divided by l and
 // rounded to bf16 once at the end.
 //
 // The frame attention score of Eq. 3 falls out of the same statistics: with the
@@ -43,6 +52,7 @@
 #include <algorithm>
 #include <cmath>
 #include <numeric>
+#include <type_traits>
 
 #include "df_internal.h"
 
@@ -60,7 +70,7 @@ constexpr int kThreads = 512;
 constexpr int kWaves = 8;
 constexpr int kBQ = kWaves * 32;   // queries per workgroup
 constexpr int kKT = 64;            // keys per LDS tile
-constexpr int kNBuf = 3;           // LDS buffers per operand
+constexpr int kNBuf = 4;           // LDS buffers per operand
 constexpr float kRescaleLog2 = 8.f;  // raise the running maximum only beyond this many powers of two
 constexpr int kXcd = 8;            // XCDs per device: consecutive workgroup ids go to consecutive XCDs
 
@@ -71,6 +81,7 @@ struct AttnParams {
   float *part;         // workspace: [H, n_qtiles, 4] partial score sums, or null
   int64_t q_st, q_sh, kc_st, kc_sh, o_st, o_sh;
   int32_t Nq, Nc, H, n_qtiles, n_units, units_per_xcd;
+  uint32_t cur_bytes;  // addressable bytes of one head's current-chunk rows: ((Nc-1)*kc_st + d) * 2
   float c;             // softmax_scale * log2(e)
   float scale;         // softmax_scale
   int64_t hist_off[kMaxHeads + 1];
@@ -109,25 +120,132 @@ __device__ __forceinline__ int key_of_row(int i) {
   return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
 }
 
-// One key tile of a head: where its rows live and how many of the 64 are real.
-struct Tile {
-  const u16 *k, *v;
-  int64_t stride;
-  int n_valid;
+
+
+// LDS layout of one 64-key tile (all sizes in bytes).  Row r lives in group r % NG at position
+// r / NG; a group is the 1 KB one buffer_load ... lds instruction writes, followed by a pad.
+template <int D>
+struct TileLayout {
+  static constexpr int ROWB = D * 2;            // bytes per row
+  static constexpr int RPG = 1024 / ROWB;       // rows per group
+  static constexpr int NG = kKT / RPG;          // groups per tile
+  static constexpr int KGS = 1024 + 16;         // K group stride
+  static constexpr int VGS = 1024 + 64;         // V group stride
+  static constexpr int KTILE = NG * KGS, VTILE = NG * VGS;
+  static constexpr int k_row(int r) { return (r % NG) * KGS + (r / NG) * ROWB; }
+  static constexpr int v_row(int r) { return (r % NG) * VGS + (r / NG) * ROWB; }
 };
+
+// ---- hand-ordered LDS operand pipeline of the MFMA phase -------------------------------
+// The LDS reads that feed the matrix core are written as asm so that their order and the
+// waits between them are fixed: kOperandDepth operands are kept in flight, every MFMA waits
+// (s_waitcnt lgkmcnt(n)) only for its own operand.  LDS returns data in issue order, so n is
+// the number of reads issued after that operand.  The waited registers pass through the wait
+// statement ("+v"), which ties each MFMA to its wait.
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+constexpr int kOperandDepth = 4;
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read_b128(unsigned addr) {
+  u32x4 r;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_read_tr16_b64(unsigned addr) {
+  u32x2 r;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
+template <int N>
+__device__ __forceinline__ void wait_lds(u32x4 &a) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void wait_lds(u32x2 &a, u32x2 &b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+__device__ __forceinline__ unsigned lds_address(const void *ptr) {
+  return unsigned(reinterpret_cast<uintptr_t>(ptr));     // low half of a flat LDS address = LDS offset
+}
+
+// One MFMA phase of a wave: S^T = K Q^T for the tile at k_addr (if DO_QK) followed by
+// O^T += V^T P^T for the tile at v_addr (if DO_PV).  k_addr / v_addr are this lane's LDS byte
+// addresses of the first A operand; all further operands are compile-time offsets from them.
+// `hook(r)` is called right after the r-th MFMA of the second product has been issued: VALU work placed
+// there runs in the shadow of the matrix core.
+template <int D, bool DO_QK, bool DO_PV, typename Hook>
+__device__ __forceinline__ void mfma_phase(unsigned k_addr, unsigned v_addr, const bf16x8 (&qf)[D / 16],
+                                           const bf16x8 (&pb)[2][2], f32x16 (&s)[2], f32x16 (&o)[D / 32],
+                                           Hook &&hook) {
+  constexpr int KS = D / 16, DB = D / 32;
+  using L = TileLayout<D>;
+  constexpr int NQK = DO_QK ? 2 * KS : 0;
+  constexpr int NPV = DO_PV ? 4 * DB : 0;
+  constexpr int NOPS = NQK + NPV;
+  u32x4 ka[NQK > 0 ? NQK : 1];
+  u32x2 va[NPV > 0 ? NPV : 1][2];
+  auto issue = [&](auto I) {
+    constexpr int i = decltype(I)::value;
+    if constexpr (i < NQK) {
+      constexpr int ks = i / 2, kb = i % 2;
+      ka[i] = lds_read_b128<L::k_row(32 * kb) + 32 * ks>(k_addr);
+    } else if constexpr (i < NOPS) {
+      constexpr int r = i - NQK, db = r % DB, ts = (r / DB) % 2, kb = r / (2 * DB);
+      constexpr int row0 = 32 * kb + 16 * ts;
+      va[r][0] = lds_read_tr16_b64<L::v_row(row0) + 64 * db>(v_addr);
+      va[r][1] = lds_read_tr16_b64<L::v_row(row0 + 4) + 64 * db>(v_addr);
+    }
+  };
+  static_for<0, (kOperandDepth < NOPS ? kOperandDepth : NOPS)>(issue);
+  __builtin_amdgcn_sched_barrier(0);
+  static_for<0, NOPS>([&](auto I) {
+    constexpr int i = decltype(I)::value;
+    // reads issued after operand i and before this point: operands i+1 .. i+kOperandDepth-1
+    constexpr int last = (i + kOperandDepth - 1 < NOPS - 1) ? i + kOperandDepth - 1 : NOPS - 1;
+    constexpr int n_qk_after = (last < NQK ? last : NQK - 1) - i > 0 ? ((last < NQK ? last : NQK - 1) - i) : 0;
+    constexpr int n_after = last - i;
+    constexpr int pending = n_qk_after * 1 + (n_after - n_qk_after) * 2;
+    if constexpr (i < NQK) {
+      constexpr int ks = i / 2, kb = i % 2;
+      wait_lds<pending>(ka[i]);
+      const bf16x8 a = __builtin_bit_cast(bf16x8, ka[i]);
+      if constexpr (ks == 0) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], zero, 0, 0, 0);
+      } else {
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+      }
+    } else {
+      constexpr int r = i - NQK, db = r % DB, ts = (r / DB) % 2, kb = r / (2 * DB);
+      wait_lds<pending>(va[r][0], va[r][1]);
+      const u32x4 a4 = {va[r][0][0], va[r][0][1], va[r][1][0], va[r][1][1]};
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a4), pb[kb][ts], o[db], 0, 0, 0);
+      hook(std::integral_constant<int, r>{});
+    }
+    issue(std::integral_constant<int, i + kOperandDepth>{});
+    __builtin_amdgcn_sched_barrier(0);      // keep wait -> MFMA -> next read in program order
+  });
+}
+
+typedef __attribute__((address_space(3))) void lds_void;
 
 template <int D, bool SCORE_ONLY>
 __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   constexpr int KS = D / 16;            // k-steps of the first product
   constexpr int DB = D / 32;            // 32-row blocks of O^T
-  constexpr int KROW = D + 8;           // K tile row, +16 B: conflict-free ds_read_b128 of 32 rows
-  constexpr int VROW = D + 32;          // V tile row, +64 B: conflict-free ds_read_b64_tr_b16
-  constexpr int KTILE = kKT * KROW, VTILE = kKT * VROW;
-  constexpr int VEC_PER_ROW = D / 8;    // 16-byte vectors per row
-  constexpr int ROWS_PER_PASS = kThreads / VEC_PER_ROW;
-  constexpr int NPASS = kKT / ROWS_PER_PASS;   // 2 for D=128, 1 for D=64
-  __shared__ __attribute__((aligned(16))) u16 lds_k[kNBuf * KTILE];
-  __shared__ __attribute__((aligned(16))) u16 lds_v[SCORE_ONLY ? 8 : kNBuf * VTILE];
+  using L = TileLayout<D>;
+  constexpr int GPW = L::NG / kWaves;   // row groups each wave loads per tile (2 for d=128, 1 for d=64)
+  constexpr int kDmaPerPhase = GPW * (SCORE_ONLY ? 1 : 2);   // buffer loads a wave issues per VALU phase
+  __shared__ __attribute__((aligned(16))) unsigned char lds_k[kNBuf * L::KTILE];
+  __shared__ __attribute__((aligned(16))) unsigned char lds_v[SCORE_ONLY ? 16 : kNBuf * L::VTILE];
   __shared__ float lds_red[kBQ * 2];
 
   // ---- which unit: XCD x (= workgroup id mod 8) takes logical units [x*upx, (x+1)*upx)
@@ -136,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   const int h = p.order[logical / p.n_qtiles];
   const int qt = logical % p.n_qtiles;
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int group = wave >> 2;
   const int j = lane & 31, hf = lane >> 5;
   const int q0 = qt * kBQ + wave * 32;
@@ -149,39 +267,41 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   const int nt1 = (len_h - sink + kKT - 1) / kKT;
   const int nt2 = (p.Nc + kKT - 1) / kKT;
   const int n_tiles = nt0 + nt1 + nt2;
-  auto tile_at = [&](int t) -> Tile {
-    Tile r;
-    if (t < nt0) {
-      const int k0 = t * kKT;
-      r.k = p.k_hist + (hoff + k0) * D; r.v = p.v_hist + (hoff + k0) * D; r.stride = D; r.n_valid = min(kKT, sink - k0);
-    } else if (t < nt0 + nt1) {
-      const int k0 = (t - nt0) * kKT;
-      r.k = p.k_hist + (hoff + sink + k0) * D; r.v = p.v_hist + (hoff + sink + k0) * D; r.stride = D;
-      r.n_valid = min(kKT, len_h - sink - k0);
-    } else {
-      const int k0 = (t - nt0 - nt1) * kKT;
-      r.k = p.k_cur + h * p.kc_sh + k0 * p.kc_st; r.v = p.v_cur + h * p.kc_sh + k0 * p.kc_st; r.stride = p.kc_st;
-      r.n_valid = min(kKT, p.Nc - k0);
-    }
-    return r;
-  };
 
-  // ---- global -> register -> LDS staging of one tile (rows past n_valid are zero-filled)
-  const int st_col = tid % VEC_PER_ROW, st_row = tid / VEC_PER_ROW;
-  auto load_tile = [&](const u16 *base, int64_t stride, int n_valid, u32x4 (&reg)[NPASS]) {
+  // ---- global -> LDS: buffer descriptors of this head's history and current-chunk rows.  A load
+  // past the end of the descriptor returns zeros, which is how partial and absent tiles are padded.
+  const uint32_t cur_stride_b = uint32_t(p.kc_st) * 2u;
+  const int hist_bytes = len_h * L::ROWB;
+  const __amdgpu_buffer_rsrc_t rs_kh = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<u16 *>(p.k_hist) + hoff * D, 0, hist_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_kc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<u16 *>(p.k_cur) + h * p.kc_sh, 0, int(p.cur_bytes), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_vh = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<u16 *>(SCORE_ONLY ? p.k_hist : p.v_hist) + hoff * D, 0, hist_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_vc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<u16 *>(SCORE_ONLY ? p.k_cur : p.v_cur) + h * p.kc_sh, 0, int(p.cur_bytes), 0x00020000);
+  // lane -> (row position inside the group, 16-byte chunk of the row) in the 1 KB a load writes
+  const int dma_pos = (16 * lane) / L::ROWB, dma_chunk = (16 * lane) % L::ROWB;
+  const int voff_hist = dma_pos * L::NG * L::ROWB + dma_chunk;
+  const int voff_cur = dma_pos * L::NG * int(cur_stride_b) + dma_chunk;
+  constexpr uint32_t kNoTile = 0x7ffff000u;      // beyond every descriptor: the load writes zeros
+  // issue this wave's share of tile t into LDS buffer `slot`
+  auto dma_tile = [&](int t, int slot, bool is_v) {
+    bool cur = false;
+    uint32_t soff = kNoTile;
+    uint32_t stride_b = L::ROWB;
+    if (t < nt0) soff = uint32_t(t * kKT) * L::ROWB;
+    else if (t < nt0 + nt1) soff = uint32_t(sink + (t - nt0) * kKT) * L::ROWB;
+    else if (t < n_tiles) { cur = true; stride_b = cur_stride_b; soff = uint32_t((t - nt0 - nt1) * kKT) * cur_stride_b; }
+    unsigned char *dst = is_v ? lds_v + slot * L::VTILE : lds_k + slot * L::KTILE;
+    const int gs = is_v ? L::VGS : L::KGS;
 #pragma unroll
-    for (int i = 0; i < NPASS; ++i) {
-      const int r = st_row + i * ROWS_PER_PASS;
-      u32x4 z = {0u, 0u, 0u, 0u};
-      reg[i] = z;
-      if (r < n_valid) reg[i] = *reinterpret_cast<const u32x4 *>(base + r * stride + 8 * st_col);
-    }
-  };
-  auto store_tile = [&](u16 *lds, int row_len, const u32x4 (&reg)[NPASS]) {
-#pragma unroll
-    for (int i = 0; i < NPASS; ++i) {
-      const int r = st_row + i * ROWS_PER_PASS;
-      *reinterpret_cast<u32x4 *>(lds + r * row_len + 8 * st_col) = reg[i];
+    for (int i = 0; i < GPW; ++i) {
+      const int g = wave + kWaves * i;
+      lds_void *d = (lds_void *)(dst + g * gs);
+      const int so = int(soff + uint32_t(g) * stride_b);
+      if (cur) __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vc : rs_kc, d, 16, voff_cur, so, 0, 0);
+      else __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vh : rs_kh, d, 16, voff_hist, so, 0, 0);
     }
   };
 
@@ -196,27 +316,20 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
   }
 
-  // ---- prologue: K(0), V(0), K(1) into LDS; K(2) and V(1) staged in registers
-  u32x4 kreg[NPASS], vreg[NPASS];
-  {
-    Tile t0 = tile_at(0);
-    load_tile(t0.k, t0.stride, t0.n_valid, kreg);
-    store_tile(lds_k, KROW, kreg);
-    if (!SCORE_ONLY) {
-      load_tile(t0.v, t0.stride, t0.n_valid, vreg);
-      store_tile(lds_v, VROW, vreg);
-    }
-    if (n_tiles > 1) {
-      Tile t1 = tile_at(1);
-      load_tile(t1.k, t1.stride, t1.n_valid, kreg);
-      store_tile(lds_k + KTILE, KROW, kreg);
-      if (!SCORE_ONLY) load_tile(t1.v, t1.stride, t1.n_valid, vreg);
-    }
-    if (n_tiles > 2) {
-      Tile t2 = tile_at(2);
-      load_tile(t2.k, t2.stride, t2.n_valid, kreg);
+  // ---- prologue: K(0..2) and V(0..1) on their way into LDS; the spare V buffer, which the first
+  // MFMA phase multiplies with P = 0, is cleared
+  dma_tile(0, 0, false);
+  dma_tile(1, 1, false);
+  dma_tile(2, 2, false);
+  if (!SCORE_ONLY) {
+    dma_tile(0, 0, true);
+    dma_tile(1, 1, true);
+    for (int i = tid; i < L::VTILE / 16; i += kThreads) {
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      *reinterpret_cast<u32x4 *>(lds_v + (kNBuf - 1) * L::VTILE + 16 * i) = z;
     }
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   lds_barrier();
   if (group == 1) lds_barrier();          // stagger: group 1 runs one phase behind group 0
 
@@ -225,90 +338,114 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-  float m = -INFINITY, l = 0.f;
+  float m = -INFINITY;
+  float l4[4] = {0.f, 0.f, 0.f, 0.f};      // independent partial row sums (summed when needed)
   float snap_m0 = -INFINITY, snap_l0 = 0.f, snap_m1 = -INFINITY, snap_l1 = 0.f;
   f32x16 s[2];
   bf16x8 pb[2][2];                         // P^T of the previous tile, [key block][16-key step]
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pb[kb][ts][e] = (__bf16)0.f;
 
-  // per-lane LDS offsets (elements) of the MFMA A operands
-  const int a_k = key_of_row(j) * KROW + 8 * hf;
+  // per-lane LDS byte addresses of the MFMA A operands (buffer 0); see TileLayout for the row placement
   const int g16 = lane >> 4, i16 = lane & 15;
-  const int a_v = (8 * (g16 >> 1) + (i16 >> 2)) * VROW + 16 * (g16 & 1) + 4 * (i16 & 3);
+  const int krow = key_of_row(j);
+  const int vrow = 8 * (g16 >> 1) + (i16 >> 2);
+  const unsigned k_lane_addr = lds_address(lds_k) + (krow % L::NG) * L::KGS + (krow / L::NG) * L::ROWB + 16 * hf;
+  const unsigned v_lane_addr = lds_address(lds_v) + (vrow % L::NG) * L::VGS + (vrow / L::NG) * L::ROWB +
+                               32 * (g16 & 1) + 8 * (i16 & 3);
+  int k_slot = 0, v_slot = kNBuf - 1;      // LDS buffer of K(t) and of V(t-1)
 
+  const int seg_end0 = nt0 - 1, seg_end1 = nt0 + nt1 - 1;
+  float mx = 0.f, mx4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
   for (int t = 0; t <= n_tiles; ++t) {
+    int n_valid_t = kKT;                    // real keys in tile t
+    if (t == seg_end0) n_valid_t = sink - (nt0 - 1) * kKT;
+    else if (t == seg_end1) n_valid_t = len_h - sink - (nt1 - 1) * kKT;
+    else if (t == n_tiles - 1) n_valid_t = p.Nc - (nt2 - 1) * kKT;
     // ================= MFMA phase =================
-    if (t < n_tiles) {
-      const u16 *kt = lds_k + (t % kNBuf) * KTILE + a_k;
+    // Always both products: at t = 0 the second one multiplies P = 0 with the zero-filled spare
+    // V buffer, at t = n_tiles the first one computes scores of a stale tile that nobody reads.
+    {
+      const unsigned k_addr = k_lane_addr + k_slot * L::KTILE;
+      const unsigned v_addr = v_lane_addr + v_slot * L::VTILE;
+      // Row maximum of tile t, computed between the MFMAs of the second product (S is complete
+      // once a few of them have been issued).  Hook slots: 3 masks a partial tile, 4..11 reduce four
+      // accumulator registers each into four independent partial maxima, 12 combines the lane pair.
+      auto tile_max_hook = [&](auto R) {
+        constexpr int r = decltype(R)::value;
+        constexpr int first = DB * 4 > 12 ? 4 : 0;
+        if constexpr (r == first - 1 || (first == 0 && r == 0)) {
+          if (n_valid_t < kKT) {            // keys past the end of the segment
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kt + 32 * kb * KROW + 16 * ks);
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
-        }
-    }
-    if (!SCORE_ONLY && t > 0) {
-      const u16 *vt = lds_v + ((t - 1) % kNBuf) * VTILE + a_v;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int ts = 0; ts < 2; ++ts)
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            const u16 *src = vt + (32 * kb + 16 * ts) * VROW + 32 * db;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 __attribute__((address_space(3))) *)(src));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 __attribute__((address_space(3))) *)(src + 4 * VROW));
-            const short a8 __attribute__((ext_vector_type(8))) = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb[kb][ts], o[db], 0, 0, 0);
+              for (int v = 0; v < 16; ++v) {
+                const int key = 32 * kb + 16 * (v >> 3) + 8 * hf + (v & 7);
+                if (key >= n_valid_t) s[kb][v] = -INFINITY;
+              }
           }
+        }
+        if constexpr (DB * 4 > 12) {
+          if constexpr (r >= first && r < first + 8) {
+            constexpr int idx = r - first, kb = idx / 4, b = (idx % 4) * 4;
+            const float a = fmaxf(fmaxf(s[kb][b], s[kb][b + 1]), s[kb][b + 2]);
+            if constexpr (kb == 0) mx4[idx % 4] = fmaxf(a, s[kb][b + 3]);
+            else mx4[idx % 4] = fmaxf(fmaxf(mx4[idx % 4], a), s[kb][b + 3]);
+          }
+          if constexpr (r == first + 8) mx = pair_max(fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3])));
+        } else {
+          if constexpr (r == DB * 4 - 1) {   // short second product (d = 64): reduce in one go
+            float a = s[0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) a = fmaxf(a, s[kb][v]);
+            mx = pair_max(a);
+          }
+        }
+      };
+      mfma_phase<D, true, !SCORE_ONLY>(k_addr, v_addr, qf, pb, s, o, tile_max_hook);
+      k_slot = (k_slot == kNBuf - 1) ? 0 : k_slot + 1;   // slot of K(t+1)
+      v_slot = (v_slot == kNBuf - 1) ? 0 : v_slot + 1;   // slot of V(t)
     }
+    // the loads of the VALU phase before last (tiles K(t+1), V(t)) must have landed before this
+    // barrier; the latest phase's loads may stay in flight
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDmaPerPhase) : "memory");
     lds_barrier();
     // ================= VALU / memory phase =================
-    // staged tiles K(t+2), V(t+1) -> LDS; then fetch K(t+3), V(t+2)
-    if (t + 2 < n_tiles) store_tile(lds_k + ((t + 2) % kNBuf) * KTILE, KROW, kreg);
-    if (!SCORE_ONLY && t + 1 < n_tiles) store_tile(lds_v + ((t + 1) % kNBuf) * VTILE, VROW, vreg);
-    if (t + 3 < n_tiles) {
-      Tile nx = tile_at(t + 3);
-      load_tile(nx.k, nx.stride, nx.n_valid, kreg);
-    }
-    if (!SCORE_ONLY && t + 2 < n_tiles) {
-      Tile nx = tile_at(t + 2);
-      load_tile(nx.v, nx.stride, nx.n_valid, vreg);
-    }
+    // always the same number of loads per phase (absent tiles load zeros), so the count above holds
+    dma_tile(t + 3, (t + 3) % kNBuf, false);
+    if (!SCORE_ONLY) dma_tile(t + 2, (t + 2) % kNBuf, true);
     if (t < n_tiles) {
-      const int seg_end0 = nt0 - 1, seg_end1 = nt0 + nt1 - 1;
-      int n_valid = kKT;
-      if (t == seg_end0) n_valid = sink - (nt0 - 1) * kKT;
-      else if (t == seg_end1) n_valid = len_h - sink - (nt1 - 1) * kKT;
-      else if (t == n_tiles - 1) n_valid = p.Nc - (nt2 - 1) * kKT;
-      if (n_valid < kKT) {                  // keys past the end of the segment
+      if (SCORE_ONLY) {                     // no second product to hide behind: reduce here
+        if (n_valid_t < kKT) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+          for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = 32 * kb + 16 * (v >> 3) + 8 * hf + (v & 7);
-            if (key >= n_valid) s[kb][v] = -INFINITY;
-          }
+            for (int v = 0; v < 16; ++v) {
+              const int key = 32 * kb + 16 * (v >> 3) + 8 * hf + (v & 7);
+              if (key >= n_valid_t) s[kb][v] = -INFINITY;
+            }
+        }
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          mx4[i4] = fmaxf(fmaxf(s[0][4 * i4], s[0][4 * i4 + 1]), fmaxf(s[0][4 * i4 + 2], s[0][4 * i4 + 3]));
+          mx4[i4] = fmaxf(mx4[i4], fmaxf(fmaxf(s[1][4 * i4], s[1][4 * i4 + 1]), fmaxf(s[1][4 * i4 + 2], s[1][4 * i4 + 3])));
+        }
+        mx = pair_max(fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3])));
       }
-      float mx = s[0][0];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
-      mx = pair_max(mx);
       // raise the running maximum only when some row of the wave outgrew it by 2^kRescaleLog2
       if (__any((mx - m) * p.c > kRescaleLog2)) {
         const float m_new = fmaxf(m, mx);
         const float alpha = fast_exp2((m - m_new) * p.c);
         m = m_new;
-        l *= alpha;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) l4[i4] *= alpha;
         if (!SCORE_ONLY) {
 #pragma unroll
           for (int db = 0; db < DB; ++db)
@@ -317,6 +454,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
         }
       }
       const float nmc = -m * p.c;
+      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -327,13 +465,13 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
             const float e0 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e], p.c, nmc));
             const float e1 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e + 1], p.c, nmc));
             w[e] = pack_bf16x2(e0, e1);
-            l += e0 + e1;
+            l4[e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e]), ones, l4[e], false);
           }
           u32x4 u = {w[0], w[1], w[2], w[3]};
           pb[kb][ts] = __builtin_bit_cast(bf16x8, u);
         }
-      if (t == seg_end0) { snap_m0 = m; snap_l0 = l; }
-      if (t == seg_end1) { snap_m1 = m; snap_l1 = l; }
+      if (t == seg_end0) { snap_m0 = m; snap_l0 = (l4[0] + l4[1]) + (l4[2] + l4[3]); }
+      if (t == seg_end1) { snap_m1 = m; snap_l1 = (l4[0] + l4[1]) + (l4[2] + l4[3]); }
     }
     lds_barrier();
   }
@@ -342,7 +480,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   if (nt1 == 0) { snap_m1 = snap_m0; snap_l1 = snap_l0; }
 
   // ---- epilogue: normalise, store, optional lse and score partials
-  const float lt = pair_sum(l);
+  const float lt = pair_sum((l4[0] + l4[1]) + (l4[2] + l4[3]));
   const float inv = 1.f / lt;
   const int row = q0 + j;
   const bool valid = row < p.Nq;
@@ -393,6 +531,7 @@ __global__ void df_score_finish_kernel(const float *part, float *score, int n_qt
   score[3 * h + 2] = (float(n_rows) - b) * inv;
 }
 
+constexpr int64_t kMaxBufferBytes = 0x7ffff000;   // one head's rows must stay below the "no tile" offset
 constexpr int kMinQTile = 128;   // smallest query tile any kernel variant uses (sizes the workspace)
 
 static size_t workspace_bytes(int H, int Nq) {
@@ -426,7 +565,7 @@ static df_status fill_heads(AttnParams &p, int H, int d, int Nq, int Nc, const i
   if (hist_off[0] != 0) return DF_ERR_RANGE;
   for (int h = 0; h < H; ++h) {
     const int64_t len = hist_off[h + 1] - hist_off[h];
-    if (len < 0 || len > INT32_MAX) return DF_ERR_RANGE;
+    if (len < 0 || len * d * 2 >= kMaxBufferBytes) return DF_ERR_RANGE;
     const int32_t sl = sink_len ? sink_len[h] : 0;
     if (sl < 0 || sl > len) return DF_ERR_RANGE;
     p.hist_off[h] = hist_off[h];
@@ -489,6 +628,8 @@ extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
   p.q_st = a->q_stride_tok; p.q_sh = a->q_stride_head;
   p.kc_st = a->kc_stride_tok; p.kc_sh = a->kc_stride_head;
   p.o_st = a->o_stride_tok; p.o_sh = a->o_stride_head;
+  if ((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2 >= kMaxBufferBytes) return DF_ERR_RANGE;
+  p.cur_bytes = uint32_t((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2);
   p.scale = a->softmax_scale;
   p.c = a->softmax_scale * 1.4426950408889634f;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -527,6 +668,8 @@ extern "C" df_status df_head_score(const df_score_args *a, void *stream) {
   p.lse = nullptr;
   p.part = static_cast<float *>(a->workspace);
   p.kc_st = a->kc_stride_tok; p.kc_sh = a->kc_stride_head;
+  if ((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2 >= kMaxBufferBytes) return DF_ERR_RANGE;
+  p.cur_bytes = uint32_t((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2);
   p.scale = a->softmax_scale;
   p.c = a->softmax_scale * 1.4426950408889634f;
   hipStream_t st = static_cast<hipStream_t>(stream);

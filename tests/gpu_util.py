@@ -10,7 +10,8 @@ MAX_ABS = 2e-2
 MEAN_ABS = 2e-3
 REL_L2 = 1e-2      # extra guard: i.i.d. values average out, so the absolute bar alone is loose
 F_ABS = 1e-4
-LSE_ABS = 2e-3
+# l sums bf16-rounded probabilities (each within 2^-9 relative), so ln l may deviate by up to 2^-8
+LSE_ABS = 5e-3
 
 
 def dev():
