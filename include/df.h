@@ -105,7 +105,9 @@ typedef struct df_attn_args {
   float *score_out;         /* DEVICE fp32 [H, 3] = (sink, neighbour, current) mass, or NULL           */
   int32_t H, d, Nq, Nc;     /* heads, head dim, queries, current-chunk keys (all > 0)                  */
   float softmax_scale;      /* the paper's equations omit it; pass 1/sqrt(d) for standard attention    */
-  void *workspace;          /* DEVICE, >= df_attn_workspace_bytes(H, d, Nq) bytes, 256-byte aligned    */
+  void *workspace;          /* DEVICE, required: >= df_attn_workspace_bytes(H, d, Nq) bytes, 256-byte
+                               aligned.  Holds the partial results of units whose keys are split
+                               between workgroups and the per-tile score sums; contents are scratch.  */
   size_t workspace_bytes;
 } df_attn_args;
 

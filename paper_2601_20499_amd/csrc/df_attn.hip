@@ -1,13 +1,20 @@
 // df_attn_fwd / df_head_score: varlen-per-head flash-style attention for gfx950.
 //
-// Work decomposition.  One workgroup of 8 wavefronts owns one (head, 256-query
-// tile) unit; each wavefront owns 32 queries and streams the head's visible
-// keys - sink region, window region, current chunk, in this order (the
-// concatenation order of Eq. 2) - in tiles of 64 keys.  A dummy head has an
-// empty history, so its units iterate the current chunk only: no masked tile
-// is ever issued.  Units are ordered longest head first and laid out so that
-// the workgroups of one XCD (workgroup id mod 8) work on neighbouring query
-// tiles of the same head and share its K/V tiles in that XCD's L2.
+// Work decomposition.  A unit is one (head, 256-query tile): 8 wavefronts of 32
+// queries each stream the head's visible keys - sink region, window region,
+// current chunk, in this order (the concatenation order of Eq. 2) - in tiles of
+// 64 keys.  A dummy head has an empty history, so its units iterate the current
+// chunk only: no masked tile is ever issued.  Heads differ in length by the ratio
+// of their contexts (3x between full and dummy heads, 20x with packed long
+// contexts), so units are not dealt out whole: all (unit, key tile) iterations,
+// heads ordered longest first, form one line that is cut into equal spans, one
+// per workgroup (one workgroup per CU).  A workgroup runs the pieces of its span
+// one after the other; a unit that lies inside one span is finished in place, a
+// unit cut by a span boundary leaves per-piece partial results (m, l, region
+// sums, unnormalised O in fp32) in the workspace and a second kernel merges
+// them in key order.  Spans are laid out so that the workgroups of one XCD
+// (workgroup id mod 8) own neighbouring spans and share K/V tiles in that
+// XCD's L2.
 //
 // MFMA mapping.  Scores are computed transposed, S^T = K Q^T, with
 // v_mfma_f32_32x32x16_bf16: the K tile is the A operand (ds_read_b128 from a
@@ -73,14 +80,19 @@ constexpr int kKT = 64;            // keys per LDS tile
 constexpr int kNBuf = 4;           // LDS buffers per operand
 constexpr float kRescaleLog2 = 8.f;  // raise the running maximum only beyond this many powers of two
 constexpr int kXcd = 8;            // XCDs per device: consecutive workgroup ids go to consecutive XCDs
+constexpr int kNumCU = 256;        // MI355X: one workgroup per CU (LDS-bound occupancy)
+constexpr int kMinSpan = 8;        // do not cut the work finer than this many tile iterations per workgroup
 
 struct AttnParams {
   const u16 *q, *k_cur, *v_cur, *k_hist, *v_hist;
   u16 *out;
   float *lse;          // [H, Nq] or null
   float *part;         // workspace: [H, n_qtiles, 4] partial score sums, or null
+  float *slots;        // workspace: 2 partial-result slots per workgroup (see slot_floats)
   int64_t q_st, q_sh, kc_st, kc_sh, o_st, o_sh;
-  int32_t Nq, Nc, H, n_qtiles, n_units, units_per_xcd;
+  int32_t Nq, Nc, H, n_qtiles, n_units;
+  int32_t n_wg, total_iters;   // workgroups (= spans) and tile iterations of the whole launch
+  int32_t cum[kMaxHeads + 1];  // first tile iteration of the hh-th longest head
   uint32_t cur_bytes;  // addressable bytes of one head's current-chunk rows: ((Nc-1)*kc_st + d) * 2
   float c;             // softmax_scale * log2(e)
   float scale;         // softmax_scale
@@ -237,6 +249,56 @@ __device__ __forceinline__ void mfma_phase(unsigned k_addr, unsigned v_addr, con
 
 typedef __attribute__((address_space(3))) void lds_void;
 
+// Partial result of one piece of a unit, as the main kernel leaves it in the workspace and the
+// merge kernel reads it back.  Both kernels use the same thread <-> element mapping, so the layout
+// is simply "in register order": per thread (m, l, l_sink, l_sink+window) and D/8 vectors of 4
+// consecutive output elements.
+template <int D>
+struct Slot {
+  static constexpr int kStats = kThreads * 4;                   // floats
+  static constexpr int kFloats = kStats + kThreads * (D / 8) * 4;
+  __device__ static float *stats(float *slot, int tid) { return slot + 4 * tid; }
+  __device__ static float *ovec(float *slot, int tid, int i) { return slot + kStats + (i * kThreads + tid) * 4; }
+};
+
+// Where the work is cut.  Span s covers tile iterations [span_begin(s), span_begin(s+1)).
+__device__ __forceinline__ int span_begin(int s, int total, int n_wg) {
+  return int((int64_t(s) * total) / n_wg);
+}
+
+// Normalise, round and store one thread's share of a finished unit; returns nothing.
+template <int D>
+__device__ __forceinline__ void store_output(const AttnParams &p, int h, int row, int hf, const f32x16 (&o)[D / 32],
+                                             float inv) {
+  u16 *dst = p.out + row * p.o_st + h * p.o_sh + 4 * hf;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int cq = 0; cq < 4; ++cq) {
+      uint2 w;
+      w.x = pack_bf16x2(o[db][4 * cq] * inv, o[db][4 * cq + 1] * inv);
+      w.y = pack_bf16x2(o[db][4 * cq + 2] * inv, o[db][4 * cq + 3] * inv);
+      *reinterpret_cast<uint2 *>(dst + 32 * db + 8 * cq) = w;
+    }
+}
+
+// Sum of the two region masses over the 256 rows of a unit, in row order (deterministic).
+__device__ __forceinline__ void reduce_masses(const AttnParams &p, float *lds_red, int h, int qt, int tid, int hf,
+                                              float mass_a, float mass_b) {
+  const int wave = tid >> 6, j = tid & 31;
+  if (hf == 0) {
+    lds_red[2 * (wave * 32 + j)] = mass_a;
+    lds_red[2 * (wave * 32 + j) + 1] = mass_b;
+  }
+  __syncthreads();
+  if (tid < 2) {
+    float acc = 0.f;
+    for (int qi = 0; qi < kBQ; ++qi) acc += lds_red[2 * qi + tid];
+    p.part[(int64_t(h) * p.n_qtiles + qt) * 4 + tid] = acc;
+  }
+  __syncthreads();
+}
+
 template <int D, bool SCORE_ONLY>
 __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   constexpr int KS = D / 16;            // k-steps of the first product
@@ -248,107 +310,15 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds_v[SCORE_ONLY ? 16 : kNBuf * L::VTILE];
   __shared__ float lds_red[kBQ * 2];
 
-  // ---- which unit: XCD x (= workgroup id mod 8) takes logical units [x*upx, (x+1)*upx)
-  const int logical = (blockIdx.x % kXcd) * p.units_per_xcd + blockIdx.x / kXcd;
-  if (logical >= p.n_units) return;
-  const int h = p.order[logical / p.n_qtiles];
-  const int qt = logical % p.n_qtiles;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int group = wave >> 2;
   const int j = lane & 31, hf = lane >> 5;
-  const int q0 = qt * kBQ + wave * 32;
 
-  // ---- tiles of this head: three segments, each cut into 64-key tiles
-  const int64_t hoff = p.hist_off[h];
-  const int len_h = int(p.hist_off[h + 1] - hoff);
-  const int sink = p.sink_len[h];
-  const int nt0 = (sink + kKT - 1) / kKT;
-  const int nt1 = (len_h - sink + kKT - 1) / kKT;
-  const int nt2 = (p.Nc + kKT - 1) / kKT;
-  const int n_tiles = nt0 + nt1 + nt2;
-
-  // ---- global -> LDS: buffer descriptors of this head's history and current-chunk rows.  A load
-  // past the end of the descriptor returns zeros, which is how partial and absent tiles are padded.
-  const uint32_t cur_stride_b = uint32_t(p.kc_st) * 2u;
-  const int hist_bytes = len_h * L::ROWB;
-  const __amdgpu_buffer_rsrc_t rs_kh = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<u16 *>(p.k_hist) + hoff * D, 0, hist_bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rs_kc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<u16 *>(p.k_cur) + h * p.kc_sh, 0, int(p.cur_bytes), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rs_vh = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<u16 *>(SCORE_ONLY ? p.k_hist : p.v_hist) + hoff * D, 0, hist_bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rs_vc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<u16 *>(SCORE_ONLY ? p.k_cur : p.v_cur) + h * p.kc_sh, 0, int(p.cur_bytes), 0x00020000);
-  // lane -> (row position inside the group, 16-byte chunk of the row) in the 1 KB a load writes
-  const int dma_pos = (16 * lane) / L::ROWB, dma_chunk = (16 * lane) % L::ROWB;
-  const int voff_hist = dma_pos * L::NG * L::ROWB + dma_chunk;
-  const int voff_cur = dma_pos * L::NG * int(cur_stride_b) + dma_chunk;
-  constexpr uint32_t kNoTile = 0x7ffff000u;      // beyond every descriptor: the load writes zeros
-  // issue this wave's share of tile t into LDS buffer `slot`
-  auto dma_tile = [&](int t, int slot, bool is_v) {
-    bool cur = false;
-    uint32_t soff = kNoTile;
-    uint32_t stride_b = L::ROWB;
-    if (t < nt0) soff = uint32_t(t * kKT) * L::ROWB;
-    else if (t < nt0 + nt1) soff = uint32_t(sink + (t - nt0) * kKT) * L::ROWB;
-    else if (t < n_tiles) { cur = true; stride_b = cur_stride_b; soff = uint32_t((t - nt0 - nt1) * kKT) * cur_stride_b; }
-    unsigned char *dst = is_v ? lds_v + slot * L::VTILE : lds_k + slot * L::KTILE;
-    const int gs = is_v ? L::VGS : L::KGS;
-#pragma unroll
-    for (int i = 0; i < GPW; ++i) {
-      const int g = wave + kWaves * i;
-      lds_void *d = (lds_void *)(dst + g * gs);
-      const int so = int(soff + uint32_t(g) * stride_b);
-      if (cur) __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vc : rs_kc, d, 16, voff_cur, so, 0, 0);
-      else __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vh : rs_kh, d, 16, voff_hist, so, 0, 0);
-    }
-  };
-
-  // ---- Q fragment: B operand of S^T = K Q^T.  Lane (j, hf) holds, for query j,
-  // elements 16*ks + 8*hf .. +7 of every k-step.
-  bf16x8 qf[KS];
-  {
-    int row = q0 + j;
-    row = row < p.Nq ? row : p.Nq - 1;          // tail rows re-read the last query; never stored
-    const u16 *src = p.q + row * p.q_st + h * p.q_sh + 8 * hf;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
-  }
-
-  // ---- prologue: K(0..2) and V(0..1) on their way into LDS; the spare V buffer, which the first
-  // MFMA phase multiplies with P = 0, is cleared
-  dma_tile(0, 0, false);
-  dma_tile(1, 1, false);
-  dma_tile(2, 2, false);
-  if (!SCORE_ONLY) {
-    dma_tile(0, 0, true);
-    dma_tile(1, 1, true);
-    for (int i = tid; i < L::VTILE / 16; i += kThreads) {
-      const u32x4 z = {0u, 0u, 0u, 0u};
-      *reinterpret_cast<u32x4 *>(lds_v + (kNBuf - 1) * L::VTILE + 16 * i) = z;
-    }
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  lds_barrier();
-  if (group == 1) lds_barrier();          // stagger: group 1 runs one phase behind group 0
-
-  f32x16 o[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-  float m = -INFINITY;
-  float l4[4] = {0.f, 0.f, 0.f, 0.f};      // independent partial row sums (summed when needed)
-  float snap_m0 = -INFINITY, snap_l0 = 0.f, snap_m1 = -INFINITY, snap_l1 = 0.f;
-  f32x16 s[2];
-  bf16x8 pb[2][2];                         // P^T of the previous tile, [key block][16-key step]
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-    for (int ts = 0; ts < 2; ++ts)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) pb[kb][ts][e] = (__bf16)0.f;
+  // ---- this workgroup's span of tile iterations; XCD x (= workgroup id mod 8) owns consecutive spans
+  const int span = (p.n_wg % kXcd == 0) ? (blockIdx.x % kXcd) * (p.n_wg / kXcd) + blockIdx.x / kXcd : blockIdx.x;
+  const int span_lo = span_begin(span, p.total_iters, p.n_wg);
+  const int span_hi = span_begin(span + 1, p.total_iters, p.n_wg);
 
   // per-lane LDS byte addresses of the MFMA A operands (buffer 0); see TileLayout for the row placement
   const int g16 = lane >> 4, i16 = lane & 15;
@@ -357,30 +327,177 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   const unsigned k_lane_addr = lds_address(lds_k) + (krow % L::NG) * L::KGS + (krow / L::NG) * L::ROWB + 16 * hf;
   const unsigned v_lane_addr = lds_address(lds_v) + (vrow % L::NG) * L::VGS + (vrow / L::NG) * L::ROWB +
                                32 * (g16 & 1) + 8 * (i16 & 3);
-  int k_slot = 0, v_slot = kNBuf - 1;      // LDS buffer of K(t) and of V(t-1)
+  // lane -> (row position inside the group, 16-byte chunk of the row) in the 1 KB a load writes
+  const int dma_pos = (16 * lane) / L::ROWB, dma_chunk = (16 * lane) % L::ROWB;
+  const uint32_t cur_stride_b = uint32_t(p.kc_st) * 2u;
+  const int voff_hist = dma_pos * L::NG * L::ROWB + dma_chunk;
+  const int voff_cur = dma_pos * L::NG * int(cur_stride_b) + dma_chunk;
+  constexpr uint32_t kNoTile = 0x7ffff000u;      // beyond every descriptor: the load writes zeros
 
-  const int seg_end0 = nt0 - 1, seg_end1 = nt0 + nt1 - 1;
-  float mx = 0.f, mx4[4] = {0.f, 0.f, 0.f, 0.f};
+  int hh = 0;                                    // index into the length-sorted head order
 #pragma unroll 1
-  for (int t = 0; t <= n_tiles; ++t) {
-    int n_valid_t = kKT;                    // real keys in tile t
-    if (t == seg_end0) n_valid_t = sink - (nt0 - 1) * kKT;
-    else if (t == seg_end1) n_valid_t = len_h - sink - (nt1 - 1) * kKT;
-    else if (t == n_tiles - 1) n_valid_t = p.Nc - (nt2 - 1) * kKT;
-    // ================= MFMA phase =================
-    // Always both products: at t = 0 the second one multiplies P = 0 with the zero-filled spare
-    // V buffer, at t = n_tiles the first one computes scores of a stale tile that nobody reads.
+  for (int pos = span_lo; pos < span_hi;) {
+    // ---- the piece at `pos`: head, query tile, first and last tile of this workgroup's share
+    while (pos >= p.cum[hh + 1]) ++hh;
+    const int h = p.order[hh];
+    const int64_t hoff = p.hist_off[h];
+    const int len_h = int(p.hist_off[h + 1] - hoff);
+    const int sink = p.sink_len[h];
+    const int nt0 = (sink + kKT - 1) / kKT;
+    const int nt1 = (len_h - sink + kKT - 1) / kKT;
+    const int nt2 = (p.Nc + kKT - 1) / kKT;
+    const int n_tiles = nt0 + nt1 + nt2;
+    const int qt = (pos - p.cum[hh]) / n_tiles;
+    const int t_begin = (pos - p.cum[hh]) % n_tiles;
+    const int t_end = min(n_tiles, t_begin + (span_hi - pos));
+    const bool whole = (t_begin == 0) && (t_end == n_tiles);
+    const int piece_pos = pos;
+    pos += t_end - t_begin;
+    const int q0 = qt * kBQ + wave * 32;
+
+    // ---- global -> LDS: buffer descriptors of this head's history and current-chunk rows.  A load
+    // past the end of the descriptor returns zeros, which is how partial and absent tiles are padded.
+    const int hist_bytes = len_h * L::ROWB;
+    const __amdgpu_buffer_rsrc_t rs_kh = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16 *>(p.k_hist) + hoff * D, 0, hist_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_kc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16 *>(p.k_cur) + h * p.kc_sh, 0, int(p.cur_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_vh = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16 *>(SCORE_ONLY ? p.k_hist : p.v_hist) + hoff * D, 0, hist_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_vc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16 *>(SCORE_ONLY ? p.k_cur : p.v_cur) + h * p.kc_sh, 0, int(p.cur_bytes), 0x00020000);
+    // issue this wave's share of tile t (zeros if the piece does not reach it) into LDS buffer `slot`
+    auto dma_tile = [&](int t, int slot, bool is_v) {
+      bool cur = false;
+      uint32_t soff = kNoTile;
+      uint32_t stride_b = L::ROWB;
+      if (t >= t_end) soff = kNoTile;
+      else if (t < nt0) soff = uint32_t(t * kKT) * L::ROWB;
+      else if (t < nt0 + nt1) soff = uint32_t(sink + (t - nt0) * kKT) * L::ROWB;
+      else { cur = true; stride_b = cur_stride_b; soff = uint32_t((t - nt0 - nt1) * kKT) * cur_stride_b; }
+      unsigned char *dst = is_v ? lds_v + slot * L::VTILE : lds_k + slot * L::KTILE;
+      const int gs = is_v ? L::VGS : L::KGS;
+#pragma unroll
+      for (int i = 0; i < GPW; ++i) {
+        const int g = wave + kWaves * i;
+        lds_void *d = (lds_void *)(dst + g * gs);
+        const int so = int(soff + uint32_t(g) * stride_b);
+        if (cur) __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vc : rs_kc, d, 16, voff_cur, so, 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vh : rs_kh, d, 16, voff_hist, so, 0, 0);
+      }
+    };
+
+    // ---- Q fragment: B operand of S^T = K Q^T.  Lane (j, hf) holds, for query j,
+    // elements 16*ks + 8*hf .. +7 of every k-step.
+    bf16x8 qf[KS];
     {
-      const unsigned k_addr = k_lane_addr + k_slot * L::KTILE;
-      const unsigned v_addr = v_lane_addr + v_slot * L::VTILE;
-      // Row maximum of tile t, computed between the MFMAs of the second product (S is complete
-      // once a few of them have been issued).  Hook slots: 3 masks a partial tile, 4..11 reduce four
-      // accumulator registers each into four independent partial maxima, 12 combines the lane pair.
-      auto tile_max_hook = [&](auto R) {
-        constexpr int r = decltype(R)::value;
-        constexpr int first = DB * 4 > 12 ? 4 : 0;
-        if constexpr (r == first - 1 || (first == 0 && r == 0)) {
-          if (n_valid_t < kKT) {            // keys past the end of the segment
+      int row = q0 + j;
+      row = row < p.Nq ? row : p.Nq - 1;          // tail rows re-read the last query; never stored
+      const u16 *src = p.q + row * p.q_st + h * p.q_sh + 8 * hf;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+    }
+
+    // ---- piece prologue: its first three K tiles and first two V tiles on their way into LDS; the
+    // spare V buffer, which the first MFMA phase multiplies with P = 0, is cleared
+    dma_tile(t_begin, 0, false);
+    dma_tile(t_begin + 1, 1, false);
+    dma_tile(t_begin + 2, 2, false);
+    if (!SCORE_ONLY) {
+      dma_tile(t_begin, 0, true);
+      dma_tile(t_begin + 1, 1, true);
+      for (int i = tid; i < L::VTILE / 16; i += kThreads) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4 *>(lds_v + (kNBuf - 1) * L::VTILE + 16 * i) = z;
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
+    if (group == 1) lds_barrier();          // stagger: group 1 runs one phase behind group 0
+
+    f32x16 o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+    float m = -INFINITY;
+    float l4[4] = {0.f, 0.f, 0.f, 0.f};      // independent partial row sums (summed when needed)
+    float snap_m0 = -INFINITY, snap_l0 = 0.f, snap_m1 = -INFINITY, snap_l1 = 0.f;
+    f32x16 s[2];
+    bf16x8 pb[2][2];                         // P^T of the previous tile, [key block][16-key step]
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pb[kb][ts][e] = (__bf16)0.f;
+    int k_slot = 0, v_slot = kNBuf - 1;      // LDS buffer of K(t) and of V(t-1)
+
+    const int seg_end0 = nt0 - 1, seg_end1 = nt0 + nt1 - 1;
+    float mx = 0.f, mx4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+    for (int t = t_begin; t <= t_end; ++t) {
+      int n_valid_t = kKT;                    // real keys in tile t
+      if (t == seg_end0) n_valid_t = sink - (nt0 - 1) * kKT;
+      else if (t == seg_end1) n_valid_t = len_h - sink - (nt1 - 1) * kKT;
+      else if (t == n_tiles - 1) n_valid_t = p.Nc - (nt2 - 1) * kKT;
+      // ================= MFMA phase =================
+      // Always both products: at the first tile the second one multiplies P = 0 with the zero-filled
+      // spare V buffer, after the last tile the first one computes scores of a stale tile that nobody reads.
+      {
+        const unsigned k_addr = k_lane_addr + k_slot * L::KTILE;
+        const unsigned v_addr = v_lane_addr + v_slot * L::VTILE;
+        // Row maximum of tile t, computed between the MFMAs of the second product (S is complete
+        // once a few of them have been issued).  Hook slots: 3 masks a partial tile, 4..11 reduce four
+        // accumulator registers each into four independent partial maxima, 12 combines the lane pair.
+        auto tile_max_hook = [&](auto R) {
+          constexpr int r = decltype(R)::value;
+          constexpr int first = DB * 4 > 12 ? 4 : 0;
+          if constexpr (r == first - 1 || (first == 0 && r == 0)) {
+            if (n_valid_t < kKT) {            // keys past the end of the segment
+#pragma unroll
+              for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                  const int key = 32 * kb + 16 * (v >> 3) + 8 * hf + (v & 7);
+                  if (key >= n_valid_t) s[kb][v] = -INFINITY;
+                }
+            }
+          }
+          if constexpr (DB * 4 > 12) {
+            if constexpr (r >= first && r < first + 8) {
+              constexpr int idx = r - first, kb = idx / 4, b = (idx % 4) * 4;
+              const float a = fmaxf(fmaxf(s[kb][b], s[kb][b + 1]), s[kb][b + 2]);
+              if constexpr (kb == 0) mx4[idx % 4] = fmaxf(a, s[kb][b + 3]);
+              else mx4[idx % 4] = fmaxf(fmaxf(mx4[idx % 4], a), s[kb][b + 3]);
+            }
+            if constexpr (r == first + 8) mx = pair_max(fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3])));
+          } else {
+            if constexpr (r == DB * 4 - 1) {   // short second product (d = 64): reduce in one go
+              float a = s[0][0];
+#pragma unroll
+              for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) a = fmaxf(a, s[kb][v]);
+              mx = pair_max(a);
+            }
+          }
+        };
+        mfma_phase<D, true, !SCORE_ONLY>(k_addr, v_addr, qf, pb, s, o, tile_max_hook);
+        k_slot = (k_slot == kNBuf - 1) ? 0 : k_slot + 1;   // slot of K(t+1)
+        v_slot = (v_slot == kNBuf - 1) ? 0 : v_slot + 1;   // slot of V(t)
+      }
+      // the loads of the VALU phase before last (tiles K(t+1), V(t)) must have landed before this
+      // barrier; the latest phase's loads may stay in flight
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDmaPerPhase) : "memory");
+      lds_barrier();
+      // ================= VALU / memory phase =================
+      // always the same number of loads per phase (absent tiles load zeros), so the count above holds
+      dma_tile(t + 3, (t + 3 - t_begin) % kNBuf, false);
+      if (!SCORE_ONLY) dma_tile(t + 2, (t + 2 - t_begin) % kNBuf, true);
+      if (t < t_end) {
+        if (SCORE_ONLY) {                     // no second product to hide behind: reduce here
+          if (n_valid_t < kKT) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -389,131 +506,160 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
                 if (key >= n_valid_t) s[kb][v] = -INFINITY;
               }
           }
-        }
-        if constexpr (DB * 4 > 12) {
-          if constexpr (r >= first && r < first + 8) {
-            constexpr int idx = r - first, kb = idx / 4, b = (idx % 4) * 4;
-            const float a = fmaxf(fmaxf(s[kb][b], s[kb][b + 1]), s[kb][b + 2]);
-            if constexpr (kb == 0) mx4[idx % 4] = fmaxf(a, s[kb][b + 3]);
-            else mx4[idx % 4] = fmaxf(fmaxf(mx4[idx % 4], a), s[kb][b + 3]);
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            mx4[i4] = fmaxf(fmaxf(s[0][4 * i4], s[0][4 * i4 + 1]), fmaxf(s[0][4 * i4 + 2], s[0][4 * i4 + 3]));
+            mx4[i4] = fmaxf(mx4[i4], fmaxf(fmaxf(s[1][4 * i4], s[1][4 * i4 + 1]), fmaxf(s[1][4 * i4 + 2], s[1][4 * i4 + 3])));
           }
-          if constexpr (r == first + 8) mx = pair_max(fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3])));
-        } else {
-          if constexpr (r == DB * 4 - 1) {   // short second product (d = 64): reduce in one go
-            float a = s[0][0];
+          mx = pair_max(fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3])));
+        }
+        // raise the running maximum only when some row of the wave outgrew it by 2^kRescaleLog2
+        if (__any((mx - m) * p.c > kRescaleLog2)) {
+          const float m_new = fmaxf(m, mx);
+          const float alpha = fast_exp2((m - m_new) * p.c);
+          m = m_new;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+          for (int i4 = 0; i4 < 4; ++i4) l4[i4] *= alpha;
+          if (!SCORE_ONLY) {
 #pragma unroll
-              for (int v = 0; v < 16; ++v) a = fmaxf(a, s[kb][v]);
-            mx = pair_max(a);
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
           }
         }
-      };
-      mfma_phase<D, true, !SCORE_ONLY>(k_addr, v_addr, qf, pb, s, o, tile_max_hook);
-      k_slot = (k_slot == kNBuf - 1) ? 0 : k_slot + 1;   // slot of K(t+1)
-      v_slot = (v_slot == kNBuf - 1) ? 0 : v_slot + 1;   // slot of V(t)
-    }
-    // the loads of the VALU phase before last (tiles K(t+1), V(t)) must have landed before this
-    // barrier; the latest phase's loads may stay in flight
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDmaPerPhase) : "memory");
-    lds_barrier();
-    // ================= VALU / memory phase =================
-    // always the same number of loads per phase (absent tiles load zeros), so the count above holds
-    dma_tile(t + 3, (t + 3) % kNBuf, false);
-    if (!SCORE_ONLY) dma_tile(t + 2, (t + 2) % kNBuf, true);
-    if (t < n_tiles) {
-      if (SCORE_ONLY) {                     // no second product to hide behind: reduce here
-        if (n_valid_t < kKT) {
+        const float nmc = -m * p.c;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int key = 32 * kb + 16 * (v >> 3) + 8 * hf + (v & 7);
-              if (key >= n_valid_t) s[kb][v] = -INFINITY;
+          for (int ts = 0; ts < 2; ++ts) {
+            unsigned w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float e0 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e], p.c, nmc));
+              const float e1 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e + 1], p.c, nmc));
+              w[e] = pack_bf16x2(e0, e1);
+              l4[e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e]), ones, l4[e], false);
             }
-        }
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          mx4[i4] = fmaxf(fmaxf(s[0][4 * i4], s[0][4 * i4 + 1]), fmaxf(s[0][4 * i4 + 2], s[0][4 * i4 + 3]));
-          mx4[i4] = fmaxf(mx4[i4], fmaxf(fmaxf(s[1][4 * i4], s[1][4 * i4 + 1]), fmaxf(s[1][4 * i4 + 2], s[1][4 * i4 + 3])));
-        }
-        mx = pair_max(fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3])));
-      }
-      // raise the running maximum only when some row of the wave outgrew it by 2^kRescaleLog2
-      if (__any((mx - m) * p.c > kRescaleLog2)) {
-        const float m_new = fmaxf(m, mx);
-        const float alpha = fast_exp2((m - m_new) * p.c);
-        m = m_new;
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) l4[i4] *= alpha;
-        if (!SCORE_ONLY) {
-#pragma unroll
-          for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
-        }
-      }
-      const float nmc = -m * p.c;
-      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int ts = 0; ts < 2; ++ts) {
-          unsigned w[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float e0 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e], p.c, nmc));
-            const float e1 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e + 1], p.c, nmc));
-            w[e] = pack_bf16x2(e0, e1);
-            l4[e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e]), ones, l4[e], false);
+            u32x4 u = {w[0], w[1], w[2], w[3]};
+            pb[kb][ts] = __builtin_bit_cast(bf16x8, u);
           }
-          u32x4 u = {w[0], w[1], w[2], w[3]};
-          pb[kb][ts] = __builtin_bit_cast(bf16x8, u);
-        }
-      if (t == seg_end0) { snap_m0 = m; snap_l0 = (l4[0] + l4[1]) + (l4[2] + l4[3]); }
-      if (t == seg_end1) { snap_m1 = m; snap_l1 = (l4[0] + l4[1]) + (l4[2] + l4[3]); }
-    }
-    lds_barrier();
-  }
-  if (group == 0) lds_barrier();          // matches group 1's extra barrier at the start
-  if (nt0 == 0) { snap_m0 = -INFINITY; snap_l0 = 0.f; }
-  if (nt1 == 0) { snap_m1 = snap_m0; snap_l1 = snap_l0; }
-
-  // ---- epilogue: normalise, store, optional lse and score partials
-  const float lt = pair_sum((l4[0] + l4[1]) + (l4[2] + l4[3]));
-  const float inv = 1.f / lt;
-  const int row = q0 + j;
-  const bool valid = row < p.Nq;
-  const float l1 = pair_sum(snap_l0 * fast_exp2((snap_m0 - m) * p.c));
-  const float l2 = pair_sum(snap_l1 * fast_exp2((snap_m1 - m) * p.c));
-  const float mass_a = valid ? l1 * inv : 0.f;     // row mass on the sink region
-  const float mass_b = valid ? l2 * inv : 0.f;     // row mass on sink + window
-  if (!SCORE_ONLY && valid) {
-    u16 *dst = p.out + row * p.o_st + h * p.o_sh + 4 * hf;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int cq = 0; cq < 4; ++cq) {
-        uint2 w;
-        w.x = pack_bf16x2(o[db][4 * cq] * inv, o[db][4 * cq + 1] * inv);
-        w.y = pack_bf16x2(o[db][4 * cq + 2] * inv, o[db][4 * cq + 3] * inv);
-        *reinterpret_cast<uint2 *>(dst + 32 * db + 8 * cq) = w;
+        if (t == seg_end0) { snap_m0 = m; snap_l0 = (l4[0] + l4[1]) + (l4[2] + l4[3]); }
+        if (t == seg_end1) { snap_m1 = m; snap_l1 = (l4[0] + l4[1]) + (l4[2] + l4[3]); }
       }
-    if (p.lse != nullptr && hf == 0) p.lse[int64_t(h) * p.Nq + row] = m * p.scale + __logf(lt);
-  }
-  if (p.part != nullptr) {
-    // deterministic block reduction: one slot per query, summed in index order by two threads
-    if (hf == 0) {
-      lds_red[2 * (wave * 32 + j)] = mass_a;
-      lds_red[2 * (wave * 32 + j) + 1] = mass_b;
+      lds_barrier();
     }
-    __syncthreads();
-    if (tid < 2) {
-      float acc = 0.f;
-      for (int qi = 0; qi < kBQ; ++qi) acc += lds_red[2 * qi + tid];
-      p.part[(int64_t(h) * p.n_qtiles + qt) * 4 + tid] = acc;
+    if (group == 0) lds_barrier();          // matches group 1's extra barrier at the start
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no load of this piece may land in the next one's tiles
+    // Region sums of this piece: a region that ended before the piece began contributes nothing, a
+    // region the piece ends in (or before) contains everything the piece has summed.
+    const float l_piece = (l4[0] + l4[1]) + (l4[2] + l4[3]);
+    if (seg_end0 >= t_end) { snap_m0 = m; snap_l0 = l_piece; }
+    if (seg_end1 >= t_end) { snap_m1 = m; snap_l1 = l_piece; }
+
+    // ---- piece epilogue
+    const float lt = pair_sum(l_piece);
+    const float l1 = pair_sum(snap_l0 * fast_exp2((snap_m0 - m) * p.c));   // sink region, relative to m
+    const float l2 = pair_sum(snap_l1 * fast_exp2((snap_m1 - m) * p.c));   // sink + window regions
+    const int row = q0 + j;
+    const bool valid = row < p.Nq;
+    if (whole) {
+      const float inv = 1.f / lt;
+      if (!SCORE_ONLY && valid) {
+        store_output<D>(p, h, row, hf, o, inv);
+        if (p.lse != nullptr && hf == 0) p.lse[int64_t(h) * p.Nq + row] = m * p.scale + __logf(lt);
+      }
+      if (p.part != nullptr)
+        reduce_masses(p, lds_red, h, qt, tid, hf, valid ? l1 * inv : 0.f, valid ? l2 * inv : 0.f);
+    } else {
+      // a piece that starts at the span's first iteration uses the span's slot 0, a later one slot 1
+      float *slot = p.slots + (int64_t(2 * span + (piece_pos == span_lo ? 0 : 1))) * Slot<D>::kFloats;
+      float4 st = {m, lt, l1, l2};
+      *reinterpret_cast<float4 *>(Slot<D>::stats(slot, tid)) = st;
+      if (!SCORE_ONLY) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int cq = 0; cq < 4; ++cq) {
+            float4 v4 = {o[db][4 * cq], o[db][4 * cq + 1], o[db][4 * cq + 2], o[db][4 * cq + 3]};
+            *reinterpret_cast<float4 *>(Slot<D>::ovec(slot, tid, db * 4 + cq)) = v4;
+          }
+      }
     }
   }
+}
+
+// Second kernel: one workgroup per unit; a unit that was cut by a span boundary is put together from
+// the partial results of its pieces, in key order, with the usual log-sum-exp weights.
+template <int D, bool SCORE_ONLY>
+__global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParams p) {
+  constexpr int DB = D / 32;
+  __shared__ float lds_red[kBQ * 2];
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63, j = lane & 31, hf = lane >> 5;
+  // unit -> head, query tile, range of tile iterations
+  int hh = 0;
+  int unit = blockIdx.x;
+  int h = p.order[0];
+  int n_tiles = 0;
+  for (;; ++hh) {
+    h = p.order[hh];
+    const int len_h = int(p.hist_off[h + 1] - p.hist_off[h]);
+    const int sink = p.sink_len[h];
+    n_tiles = (sink + kKT - 1) / kKT + (len_h - sink + kKT - 1) / kKT + (p.Nc + kKT - 1) / kKT;
+    if (unit < p.n_qtiles) break;
+    unit -= p.n_qtiles;
+  }
+  const int qt = unit;
+  const int u_lo = p.cum[hh] + qt * n_tiles, u_hi = u_lo + n_tiles;
+  // spans that hold the first and the last iteration of the unit
+  int s_lo = int((int64_t(u_lo) * p.n_wg) / p.total_iters);
+  while (span_begin(s_lo + 1, p.total_iters, p.n_wg) <= u_lo) ++s_lo;
+  while (span_begin(s_lo, p.total_iters, p.n_wg) > u_lo) --s_lo;
+  int s_hi = s_lo;
+  while (span_begin(s_hi + 1, p.total_iters, p.n_wg) < u_hi) ++s_hi;
+  if (s_lo == s_hi) return;                       // the unit was finished in place
+
+  float M = -INFINITY, Lt = 0.f, La = 0.f, Lb = 0.f;
+  f32x16 o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+#pragma unroll 1
+  for (int sp = s_lo; sp <= s_hi; ++sp) {
+    const int b = span_begin(sp, p.total_iters, p.n_wg);
+    const int piece_lo = max(u_lo, b);
+    const float *slot = p.slots + (int64_t(2 * sp + (piece_lo == b ? 0 : 1))) * Slot<D>::kFloats;
+    const float4 st = *reinterpret_cast<const float4 *>(Slot<D>::stats(const_cast<float *>(slot), tid));
+    const float m_new = fmaxf(M, st.x);
+    const float w_old = fast_exp2((M - m_new) * p.c), w_new = fast_exp2((st.x - m_new) * p.c);
+    M = m_new;
+    Lt = Lt * w_old + st.y * w_new;
+    La = La * w_old + st.z * w_new;
+    Lb = Lb * w_old + st.w * w_new;
+    if (!SCORE_ONLY) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int cq = 0; cq < 4; ++cq) {
+          const float4 v4 = *reinterpret_cast<const float4 *>(Slot<D>::ovec(const_cast<float *>(slot), tid, db * 4 + cq));
+          o[db][4 * cq] = o[db][4 * cq] * w_old + v4.x * w_new;
+          o[db][4 * cq + 1] = o[db][4 * cq + 1] * w_old + v4.y * w_new;
+          o[db][4 * cq + 2] = o[db][4 * cq + 2] * w_old + v4.z * w_new;
+          o[db][4 * cq + 3] = o[db][4 * cq + 3] * w_old + v4.w * w_new;
+        }
+    }
+  }
+  const float inv = 1.f / Lt;
+  const int row = qt * kBQ + wave * 32 + j;
+  const bool valid = row < p.Nq;
+  if (!SCORE_ONLY && valid) {
+    store_output<D>(p, h, row, hf, o, inv);
+    if (p.lse != nullptr && hf == 0) p.lse[int64_t(h) * p.Nq + row] = M * p.scale + __logf(Lt);
+  }
+  if (p.part != nullptr)
+    reduce_masses(p, lds_red, h, qt, tid, hf, valid ? La * inv : 0.f, valid ? Lb * inv : 0.f);
 }
 
 // F[h] = (sum_a, sum_b - sum_a, n - sum_b) / n over the head's query tiles, in tile order.
@@ -534,19 +680,45 @@ __global__ void df_score_finish_kernel(const float *part, float *score, int n_qt
 constexpr int64_t kMaxBufferBytes = 0x7ffff000;   // one head's rows must stay below the "no tile" offset
 constexpr int kMinQTile = 128;   // smallest query tile any kernel variant uses (sizes the workspace)
 
-static size_t workspace_bytes(int H, int Nq) {
+// Workspace layout: [score partials: H * ceil(Nq/128) * 4 floats, rounded up to 256 B]
+//                   [partial-result slots: 2 per workgroup, kNumCU workgroups at most]
+static size_t part_bytes(int H, int Nq) {
   const size_t tiles = (size_t(Nq) + kMinQTile - 1) / kMinQTile;
-  return ((size_t(H) * tiles * 4 * sizeof(float) + 255) / 256) * 256 + 256;
+  return ((size_t(H) * tiles * 4 * sizeof(float) + 255) / 256) * 256;
+}
+static size_t slot_bytes(int d) {
+  return size_t(d == 128 ? Slot<128>::kFloats : Slot<64>::kFloats) * sizeof(float);
+}
+static size_t workspace_bytes(int H, int d, int Nq) {
+  return part_bytes(H, Nq) + 2 * size_t(kNumCU) * slot_bytes(d);
 }
 
 template <int D, bool SCORE_ONLY>
-static df_status launch(AttnParams &p, float *score_out, hipStream_t st) {
+static df_status launch(AttnParams &p, void *workspace, float *score_out, hipStream_t st) {
   p.n_qtiles = (p.Nq + kBQ - 1) / kBQ;
   p.n_units = p.n_qtiles * p.H;
-  p.units_per_xcd = (p.n_units + kXcd - 1) / kXcd;
-  dim3 grid(p.units_per_xcd * kXcd);
-  hipLaunchKernelGGL((df_attn_kernel<D, SCORE_ONLY>), grid, dim3(kThreads), 0, st, p);
+  // the line of tile iterations: heads longest first, query tiles of a head next to each other
+  int64_t total = 0;
+  for (int hh = 0; hh < p.H; ++hh) {
+    const int h = p.order[hh];
+    const int64_t len = p.hist_off[h + 1] - p.hist_off[h];
+    const int64_t sink = p.sink_len[h];
+    const int64_t nt = (sink + kKT - 1) / kKT + (len - sink + kKT - 1) / kKT + (p.Nc + kKT - 1) / kKT;
+    p.cum[hh] = int32_t(total);
+    total += nt * p.n_qtiles;
+    if (total > INT32_MAX / 2) return DF_ERR_RANGE;
+  }
+  p.cum[p.H] = int32_t(total);
+  p.total_iters = int32_t(total);
+  p.n_wg = int32_t(std::max<int64_t>(1, std::min<int64_t>(kNumCU, total / kMinSpan)));
+  p.part = score_out ? static_cast<float *>(workspace) : nullptr;
+  p.slots = reinterpret_cast<float *>(static_cast<char *>(workspace) + part_bytes(p.H, p.Nq));
+  hipLaunchKernelGGL((df_attn_kernel<D, SCORE_ONLY>), dim3(p.n_wg), dim3(kThreads), 0, st, p);
   if (df_status s = launch_status()) return s;
+  if (p.n_wg > 1) {
+    hipLaunchKernelGGL((df_attn_merge_kernel<D, SCORE_ONLY>), dim3(p.n_units), dim3(kThreads), 0, st, p);
+    if (df_status s = launch_status()) return s;
+  }
   if (score_out) {
     hipLaunchKernelGGL(df_score_finish_kernel, dim3(p.H), dim3(64), 0, st, p.part, score_out, p.n_qtiles, p.Nq);
     if (df_status s = launch_status()) return s;
@@ -593,9 +765,8 @@ static df_status fill_heads(AttnParams &p, int H, int d, int Nq, int Nc, const i
 using namespace df;
 
 extern "C" size_t df_attn_workspace_bytes(int32_t H, int32_t d, int32_t Nq) {
-  (void)d;
-  if (H <= 0 || Nq <= 0) return 0;
-  return workspace_bytes(H, Nq);
+  if (H <= 0 || Nq <= 0 || (d != 64 && d != 128)) return 0;
+  return workspace_bytes(H, d, Nq);
 }
 
 extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
@@ -612,11 +783,8 @@ extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
       (multi && (!stride_ok(a->q_stride_head) || !stride_ok(a->kc_stride_head) || !stride_ok(a->o_stride_head))))
     return DF_ERR_ALIGN;
   if (!(a->softmax_scale > 0.f) || !std::isfinite(a->softmax_scale)) return DF_ERR_RANGE;
-  if (a->score_out) {
-    if (!a->workspace) return DF_ERR_WORKSPACE;
-    if (a->workspace_bytes < workspace_bytes(a->H, a->Nq)) return DF_ERR_WORKSPACE;
-    if (reinterpret_cast<uintptr_t>(a->workspace) & 255u) return DF_ERR_ALIGN;
-  }
+  if (!a->workspace || a->workspace_bytes < workspace_bytes(a->H, a->d, a->Nq)) return DF_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(a->workspace) & 255u) return DF_ERR_ALIGN;
   p.q = static_cast<const u16 *>(a->q);
   p.k_cur = static_cast<const u16 *>(a->k_cur);
   p.v_cur = static_cast<const u16 *>(a->v_cur);
@@ -624,7 +792,6 @@ extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
   p.v_hist = static_cast<const u16 *>(a->v_hist);
   p.out = static_cast<u16 *>(a->out);
   p.lse = a->lse_out;
-  p.part = a->score_out ? static_cast<float *>(a->workspace) : nullptr;
   p.q_st = a->q_stride_tok; p.q_sh = a->q_stride_head;
   p.kc_st = a->kc_stride_tok; p.kc_sh = a->kc_stride_head;
   p.o_st = a->o_stride_tok; p.o_sh = a->o_stride_head;
@@ -633,8 +800,8 @@ extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
   p.scale = a->softmax_scale;
   p.c = a->softmax_scale * 1.4426950408889634f;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (a->d == 128) return launch<128, false>(p, a->score_out, st);
-  return launch<64, false>(p, a->score_out, st);
+  if (a->d == 128) return launch<128, false>(p, a->workspace, a->score_out, st);
+  return launch<64, false>(p, a->workspace, a->score_out, st);
 }
 
 extern "C" df_status df_head_score(const df_score_args *a, void *stream) {
@@ -652,7 +819,7 @@ extern "C" df_status df_head_score(const df_score_args *a, void *stream) {
       (multi && (!stride_ok(a->q_stride_head) || !stride_ok(a->kc_stride_head))))
     return DF_ERR_ALIGN;
   if (!(a->softmax_scale > 0.f) || !std::isfinite(a->softmax_scale)) return DF_ERR_RANGE;
-  if (!a->workspace || a->workspace_bytes < workspace_bytes(a->H, a->Nq)) return DF_ERR_WORKSPACE;
+  if (!a->workspace || a->workspace_bytes < workspace_bytes(a->H, a->d, a->Nq)) return DF_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(a->workspace) & 255u) return DF_ERR_ALIGN;
   // the sampled queries are a strided view of Q
   const int n_samp = (a->Nq - a->q_offset + a->q_sample_stride - 1) / a->q_sample_stride;
@@ -666,13 +833,12 @@ extern "C" df_status df_head_score(const df_score_args *a, void *stream) {
   p.v_hist = nullptr;
   p.out = nullptr;
   p.lse = nullptr;
-  p.part = static_cast<float *>(a->workspace);
   p.kc_st = a->kc_stride_tok; p.kc_sh = a->kc_stride_head;
   if ((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2 >= kMaxBufferBytes) return DF_ERR_RANGE;
   p.cur_bytes = uint32_t((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2);
   p.scale = a->softmax_scale;
   p.c = a->softmax_scale * 1.4426950408889634f;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (a->d == 128) return launch<128, true>(p, a->score_out, st);
-  return launch<64, true>(p, a->score_out, st);
+  if (a->d == 128) return launch<128, true>(p, a->workspace, a->score_out, st);
+  return launch<64, true>(p, a->workspace, a->score_out, st);
 }

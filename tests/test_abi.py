@@ -115,6 +115,7 @@ def _attn_args(b, **kw):
     a.q_stride_head = a.kc_stride_head = a.o_stride_head = 128
     a.H, a.d, a.Nq, a.Nc = 4, 128, 100, 100
     a.softmax_scale = 0.1
+    a.workspace, a.workspace_bytes = 0x40000, 1 << 30
     keep = {"off": (C.c_int64 * 5)(0, 10, 10, 30, 40), "sl": (C.c_int32 * 4)(5, 0, 20, 0)}
     a.hist_off, a.hist_sink_len = keep["off"], keep["sl"]
     for k, v in kw.items():
@@ -135,8 +136,9 @@ def test_attn_argument_validation(b):
         (dict(q_stride_tok=100), E.DF_ERR_ALIGN),
         (dict(k_hist=None), E.DF_ERR_NULL),
         (dict(softmax_scale=0.0), E.DF_ERR_RANGE),
-        (dict(score_out=0x20000), E.DF_ERR_WORKSPACE),                       # score wanted, no workspace
-        (dict(score_out=0x20000, workspace=0x30000, workspace_bytes=8), E.DF_ERR_WORKSPACE),
+        (dict(workspace=None), E.DF_ERR_WORKSPACE),                          # the workspace is always required
+        (dict(workspace=0x30000, workspace_bytes=8), E.DF_ERR_WORKSPACE),
+        (dict(workspace=0x30010), E.DF_ERR_ALIGN),
     ]
     for kw, code in cases:
         a, keep = _attn_args(b, **kw)
@@ -150,7 +152,7 @@ def test_attn_argument_validation(b):
     a, keep = _attn_args(b, hist_off=None)
     assert b.lib.df_attn_fwd(C.byref(a), None) == E.DF_ERR_NULL
     assert b.lib.df_attn_fwd(None, None) == E.DF_ERR_NULL
-    assert b.df_attn_workspace_bytes(12, 128, 4680) >= 12 * 37 * 16
+    assert b.df_attn_workspace_bytes(12, 128, 4680) >= 12 * 37 * 16 + 512 * 512 * 132
     assert b.df_attn_workspace_bytes(0, 128, 10) == 0
 
 

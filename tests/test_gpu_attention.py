@@ -88,9 +88,12 @@ def test_bitwise_determinism_and_no_out_of_bounds_writes(df):
     pad = 5
     big = torch.full((w.Nq + 2 * pad, w.H, w.d), 7.0, dtype=torch.bfloat16, device=d)
     outs = []
+    ws = torch.empty(df.df_attn_workspace_bytes(w.H, w.d, w.Nq), dtype=torch.uint8, device=d)
     for _ in range(2):
         big.fill_(7.0)
-        df.df_attn_fwd(q, w.k_cur.to(d), w.v_cur.to(d), kp.to(d), vp.to(d), off, sl, big[pad:pad + w.Nq], w.scale)
+        ws.fill_(0xAB)
+        df.df_attn_fwd(q, w.k_cur.to(d), w.v_cur.to(d), kp.to(d), vp.to(d), off, sl, big[pad:pad + w.Nq], w.scale,
+                       workspace=ws)
         torch.cuda.synchronize()
         outs.append(big.clone())
     assert torch.equal(outs[0], outs[1])

@@ -84,13 +84,14 @@ def test_append_pack_attention_chain(df):
     cap_rows = sum(sink_cap) + sum(win_cap)
     k_out = torch.zeros(cap_rows, d, dtype=torch.bfloat16, device=gu.dev())
     v_out = torch.zeros(cap_rows, d, dtype=torch.bfloat16, device=gu.dev())
+    ws = torch.empty(df.df_attn_workspace_bytes(H, d, C * T), dtype=torch.uint8, device=gu.dev())
     for step in range(4):
         q = (torch.randn(C * T, H, d, generator=g) + 0.3).to(torch.bfloat16)
         kc = torch.randn(C * T, H, d, generator=g).to(torch.bfloat16)
         vc = torch.randn(C * T, H, d, generator=g).to(torch.bfloat16)
         off, sl = df.df_pack_context(cache, sink_cap, win_cap, k_out, v_out)
         out = torch.empty(C * T, H, d, dtype=torch.bfloat16, device=gu.dev())
-        df.df_attn_fwd(q.to(gu.dev()), kc.to(gu.dev()), vc.to(gu.dev()), k_out, v_out, off, sl, out, scale)
+        df.df_attn_fwd(q.to(gu.dev()), kc.to(gu.dev()), vc.to(gu.dev()), k_out, v_out, off, sl, out, scale, workspace=ws)
         df.df_kv_append(cache, kc.to(gu.dev()), vc.to(gu.dev()))
         torch.cuda.synchronize()
         ref, _, _ = orc.layer_attention(q.double().numpy(), hist_k, hist_v, kc.double().numpy(), vc.double().numpy(),
