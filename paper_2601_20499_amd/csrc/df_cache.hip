@@ -39,51 +39,46 @@ struct CopyParams {
 };
 
 constexpr int kCopyThreads = 256;
-constexpr int kRowsPerBlock = 64;
+constexpr int kVecPerBlock = 1024;     // 16-byte vectors per workgroup: 4 per thread, 64 rows of d = 128
 
 template <bool APPEND>
 __global__ __launch_bounds__(kCopyThreads) void df_rows_kernel(const CopyParams p) {
   const HeadPlan &pl = p.plan[blockIdx.y];
-  const int n_rows = pl.n_a + pl.n_b;
-  const int row0 = blockIdx.x * kRowsPerBlock;
-  if (row0 >= n_rows) return;
+  const int rv = p.row_vec;
+  const int n_vec = (pl.n_a + pl.n_b) * rv;
+  const int v0 = blockIdx.x * kVecPerBlock + threadIdx.x;
+  if (blockIdx.x * kVecPerBlock >= n_vec) return;
   const vec16 *__restrict__ src = blockIdx.z ? p.src_v : p.src_k;
   vec16 *__restrict__ dst = blockIdx.z ? p.dst_v : p.dst_k;
-  const int rv = p.row_vec;
-  const int lanes_rows = kCopyThreads / rv;          // rows covered per pass
-  const int col = threadIdx.x % rv;
-  const int rsub = threadIdx.x / rv;
-  constexpr int kMaxPasses = kRowsPerBlock / (kCopyThreads / 16);   // d = 128 -> 16 rows per pass
-  vec16 val[kMaxPasses];
-  int64_t daddr[kMaxPasses];
-  const int passes = kRowsPerBlock / lanes_rows;
+  constexpr int kPer = kVecPerBlock / kCopyThreads;
+  vec16 val[kPer];
+  int64_t daddr[kPer];
 #pragma unroll
-  for (int it = 0; it < kMaxPasses; ++it) {
+  for (int it = 0; it < kPer; ++it) {
+    const int v = v0 + it * kCopyThreads;
     daddr[it] = -1;
-    if (it < passes) {
-      const int i = row0 + it * lanes_rows + rsub;
-      if (i < n_rows) {
-        int64_t s_row, d_row;
-        if (i < pl.n_a) {
-          s_row = pl.a_src + i;
-          d_row = pl.a_dst + i;
-        } else {
-          const int j = i - pl.n_a;
-          int slot = pl.ring_start + j;
-          if (slot >= pl.ring_cap) slot -= pl.ring_cap;
-          if (APPEND) { s_row = pl.b_lin + j; d_row = pl.ring_base + slot; }
-          else        { s_row = pl.ring_base + slot; d_row = pl.b_lin + j; }
-        }
-        const int64_t saddr = APPEND ? s_row * p.src_stride_tok + int64_t(pl.head) * p.src_stride_head + col
-                                     : s_row * int64_t(rv) + col;
-        val[it] = __builtin_nontemporal_load(src + saddr);
-        daddr[it] = d_row * int64_t(rv) + col;
+    if (v < n_vec) {
+      const int i = v / rv, col = v - i * rv;
+      int64_t s_row, d_row;
+      if (i < pl.n_a) {
+        s_row = pl.a_src + i;
+        d_row = pl.a_dst + i;
+      } else {
+        const int j = i - pl.n_a;
+        int slot = pl.ring_start + j;
+        if (slot >= pl.ring_cap) slot -= pl.ring_cap;
+        if (APPEND) { s_row = pl.b_lin + j; d_row = pl.ring_base + slot; }
+        else        { s_row = pl.ring_base + slot; d_row = pl.b_lin + j; }
       }
+      const int64_t saddr = APPEND ? s_row * p.src_stride_tok + int64_t(pl.head) * p.src_stride_head + col
+                                   : s_row * int64_t(rv) + col;
+      val[it] = src[saddr];
+      daddr[it] = d_row * int64_t(rv) + col;
     }
   }
 #pragma unroll
-  for (int it = 0; it < kMaxPasses; ++it)
-    if (daddr[it] >= 0) __builtin_nontemporal_store(val[it], dst + daddr[it]);
+  for (int it = 0; it < kPer; ++it)
+    if (daddr[it] >= 0) dst[daddr[it]] = val[it];
 }
 
 static df_status check_cache(const df_cache *c) {
@@ -159,7 +154,7 @@ extern "C" df_status df_kv_append(const df_append_args *a, void *stream) {
   }
   p.n_plans = np;
   if (np > 0) {
-    dim3 grid((max_rows + kRowsPerBlock - 1) / kRowsPerBlock, np, 2);
+    dim3 grid((max_rows * p.row_vec + kVecPerBlock - 1) / kVecPerBlock, np, 2);
     hipLaunchKernelGGL(df_rows_kernel<true>, grid, dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream), p);
     if (df_status s = launch_status()) return s;
   }
@@ -215,7 +210,7 @@ extern "C" df_status df_pack_context(const df_pack_args *a, void *stream) {
   }
   p.n_plans = np;
   if (np > 0) {
-    dim3 grid((max_rows + kRowsPerBlock - 1) / kRowsPerBlock, np, 2);
+    dim3 grid((max_rows * p.row_vec + kVecPerBlock - 1) / kVecPerBlock, np, 2);
     hipLaunchKernelGGL(df_rows_kernel<false>, grid, dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream), p);
     if (df_status s = launch_status()) return s;
   }
