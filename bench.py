@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config4", "config5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="oracle rows per head (0 = sized for ~15 s)")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (known traffic, calibrates FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -148,6 +150,12 @@ def main():
         df.df_kv_append(cb, st["k_cur"], st["v_cur"])
         m[4].record()
 
+    if args.calib_copy_mb:
+        src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads and writes calib_copy_mb MiB each
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(W):
         one_step(i)
     torch.cuda.synchronize()

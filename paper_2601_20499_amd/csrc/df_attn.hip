@@ -6,15 +6,16 @@
 // 64 keys.  A dummy head has an empty history, so its units iterate the current
 // chunk only: no masked tile is ever issued.  Heads differ in length by the ratio
 // of their contexts (3x between full and dummy heads, 20x with packed long
-// contexts), so units are not dealt out whole: all (unit, key tile) iterations,
-// heads ordered longest first, form one line that is cut into equal spans, one
-// per workgroup (one workgroup per CU).  A workgroup runs the pieces of its span
-// one after the other; a unit that lies inside one span is finished in place, a
-// unit cut by a span boundary leaves per-piece partial results (m, l, region
-// sums, unnormalised O in fp32) in the workspace and a second kernel merges
-// them in key order.  Spans are laid out so that the workgroups of one XCD
-// (workgroup id mod 8) own neighbouring spans and share K/V tiles in that
-// XCD's L2.
+// contexts), so heads are not dealt out whole.  The key tiles of all heads,
+// longest head first, form one line of "columns"; the line is cut into equal
+// spans, one per TEAM of workgroups.  A team has one workgroup per query tile:
+// its members walk the same columns at the same time, each for its own 256
+// queries, so they share every K/V tile in L2 while it is hot, and every team
+// does the same amount of work.  A head that lies inside one span is finished
+// in place; a head cut by a span boundary leaves per-piece partial results
+// (m, l, region sums, unnormalised O in fp32) in the workspace and a second
+// kernel merges them in key order.  Teams are laid out XCD-major (workgroup id
+// mod 8 selects the XCD), so a team sits on one or two XCDs.
 //
 // MFMA mapping.  Scores are computed transposed, S^T = K Q^T, with
 // v_mfma_f32_32x32x16_bf16: the K tile is the A operand (ds_read_b128 from a
@@ -81,7 +82,7 @@ constexpr int kNBuf = 4;           // LDS buffers per operand
 constexpr float kRescaleLog2 = 8.f;  // raise the running maximum only beyond this many powers of two
 constexpr int kXcd = 8;            // XCDs per device: consecutive workgroup ids go to consecutive XCDs
 constexpr int kNumCU = 256;        // MI355X: one workgroup per CU (LDS-bound occupancy)
-constexpr int kMinSpan = 8;        // do not cut the work finer than this many tile iterations per workgroup
+constexpr int kMinSpan = 8;        // do not cut the work finer than this many key tiles per team
 
 struct AttnParams {
   const u16 *q, *k_cur, *v_cur, *k_hist, *v_hist;
@@ -91,8 +92,9 @@ struct AttnParams {
   float *slots;        // workspace: 2 partial-result slots per workgroup (see slot_floats)
   int64_t q_st, q_sh, kc_st, kc_sh, o_st, o_sh;
   int32_t Nq, Nc, H, n_qtiles, n_units;
-  int32_t n_wg, total_iters;   // workgroups (= spans) and tile iterations of the whole launch
-  int32_t cum[kMaxHeads + 1];  // first tile iteration of the hh-th longest head
+  int32_t team_size, n_teams, rounds;   // query tiles per team pass, teams (= spans), passes over the query tiles
+  int32_t total_cols;          // key tiles of all heads
+  int32_t cum[kMaxHeads + 1];  // first column of the hh-th longest head
   uint32_t cur_bytes;  // addressable bytes of one head's current-chunk rows: ((Nc-1)*kc_st + d) * 2
   float c;             // softmax_scale * log2(e)
   float scale;         // softmax_scale
@@ -261,7 +263,12 @@ struct Slot {
   __device__ static float *ovec(float *slot, int tid, int i) { return slot + kStats + (i * kThreads + tid) * 4; }
 };
 
-// Where the work is cut.  Span s covers tile iterations [span_begin(s), span_begin(s+1)).
+// Partial-result slot of (span, first or later piece of the span, query tile).
+__device__ __forceinline__ int64_t slot_index(const AttnParams &p, int span, int which, int qt) {
+  return (int64_t(2 * span + which) * p.rounds + qt / p.team_size) * p.team_size + qt % p.team_size;
+}
+
+// Where the work is cut.  Span s covers columns [span_begin(s), span_begin(s+1)).
 __device__ __forceinline__ int span_begin(int s, int total, int n_wg) {
   return int((int64_t(s) * total) / n_wg);
 }
@@ -315,10 +322,13 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   const int group = wave >> 2;
   const int j = lane & 31, hf = lane >> 5;
 
-  // ---- this workgroup's span of tile iterations; XCD x (= workgroup id mod 8) owns consecutive spans
-  const int span = (p.n_wg % kXcd == 0) ? (blockIdx.x % kXcd) * (p.n_wg / kXcd) + blockIdx.x / kXcd : blockIdx.x;
-  const int span_lo = span_begin(span, p.total_iters, p.n_wg);
-  const int span_hi = span_begin(span + 1, p.total_iters, p.n_wg);
+  // ---- this workgroup's team (span of columns) and member index (query tile); XCD-major numbering
+  const int n_slots_x = int(gridDim.x) / kXcd;
+  const int wg = (gridDim.x % kXcd == 0) ? (blockIdx.x % kXcd) * n_slots_x + blockIdx.x / kXcd : blockIdx.x;
+  const int span = wg / p.team_size, member = wg % p.team_size;
+  if (span >= p.n_teams) return;
+  const int span_lo = span_begin(span, p.total_cols, p.n_teams);
+  const int span_hi = span_begin(span + 1, p.total_cols, p.n_teams);
 
   // per-lane LDS byte addresses of the MFMA A operands (buffer 0); see TileLayout for the row placement
   const int g16 = lane >> 4, i16 = lane & 15;
@@ -332,12 +342,16 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   const uint32_t cur_stride_b = uint32_t(p.kc_st) * 2u;
   const int voff_hist = dma_pos * L::NG * L::ROWB + dma_chunk;
   const int voff_cur = dma_pos * L::NG * int(cur_stride_b) + dma_chunk;
-  constexpr uint32_t kNoTile = 0x7ffff000u;      // beyond every descriptor: the load writes zeros
+  constexpr uint32_t kNoTile = 0x7ff00000u;      // beyond every descriptor (plus any lane offset): the load writes zeros
 
+#pragma unroll 1
+  for (int round = 0; round < p.rounds; ++round) {
+  const int qt = round * p.team_size + member;   // this workgroup's query tile in this pass
+  if (qt >= p.n_qtiles) break;
   int hh = 0;                                    // index into the length-sorted head order
 #pragma unroll 1
   for (int pos = span_lo; pos < span_hi;) {
-    // ---- the piece at `pos`: head, query tile, first and last tile of this workgroup's share
+    // ---- the piece at `pos`: head, first and last tile of this team's share
     while (pos >= p.cum[hh + 1]) ++hh;
     const int h = p.order[hh];
     const int64_t hoff = p.hist_off[h];
@@ -347,8 +361,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     const int nt1 = (len_h - sink + kKT - 1) / kKT;
     const int nt2 = (p.Nc + kKT - 1) / kKT;
     const int n_tiles = nt0 + nt1 + nt2;
-    const int qt = (pos - p.cum[hh]) / n_tiles;
-    const int t_begin = (pos - p.cum[hh]) % n_tiles;
+    const int t_begin = pos - p.cum[hh];
     const int t_end = min(n_tiles, t_begin + (span_hi - pos));
     const bool whole = (t_begin == 0) && (t_end == n_tiles);
     const int piece_pos = pos;
@@ -366,24 +379,26 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
         const_cast<u16 *>(SCORE_ONLY ? p.k_hist : p.v_hist) + hoff * D, 0, hist_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_vc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16 *>(SCORE_ONLY ? p.k_cur : p.v_cur) + h * p.kc_sh, 0, int(p.cur_bytes), 0x00020000);
-    // issue this wave's share of tile t (zeros if the piece does not reach it) into LDS buffer `slot`
+    // Issue this wave's share of tile t (zeros if the piece does not reach it) into LDS buffer `slot`.
+    // The whole byte offset travels in the VGPR offset, the only part of a buffer address that the
+    // hardware checks against the descriptor's size (the SGPR offset is not range-checked).
     auto dma_tile = [&](int t, int slot, bool is_v) {
       bool cur = false;
-      uint32_t soff = kNoTile;
+      uint32_t toff = kNoTile;
       uint32_t stride_b = L::ROWB;
-      if (t >= t_end) soff = kNoTile;
-      else if (t < nt0) soff = uint32_t(t * kKT) * L::ROWB;
-      else if (t < nt0 + nt1) soff = uint32_t(sink + (t - nt0) * kKT) * L::ROWB;
-      else { cur = true; stride_b = cur_stride_b; soff = uint32_t((t - nt0 - nt1) * kKT) * cur_stride_b; }
+      if (t >= t_end) toff = kNoTile;
+      else if (t < nt0) toff = uint32_t(t * kKT) * L::ROWB;
+      else if (t < nt0 + nt1) toff = uint32_t(sink + (t - nt0) * kKT) * L::ROWB;
+      else { cur = true; stride_b = cur_stride_b; toff = uint32_t((t - nt0 - nt1) * kKT) * cur_stride_b; }
       unsigned char *dst = is_v ? lds_v + slot * L::VTILE : lds_k + slot * L::KTILE;
       const int gs = is_v ? L::VGS : L::KGS;
 #pragma unroll
       for (int i = 0; i < GPW; ++i) {
         const int g = wave + kWaves * i;
         lds_void *d = (lds_void *)(dst + g * gs);
-        const int so = int(soff + uint32_t(g) * stride_b);
-        if (cur) __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vc : rs_kc, d, 16, voff_cur, so, 0, 0);
-        else __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vh : rs_kh, d, 16, voff_hist, so, 0, 0);
+        const int vo = int(toff + uint32_t(g) * stride_b + uint32_t(cur ? voff_cur : voff_hist));
+        if (cur) __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vc : rs_kc, d, 16, vo, 0, 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vh : rs_kh, d, 16, vo, 0, 0, 0);
       }
     };
 
@@ -573,7 +588,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
         reduce_masses(p, lds_red, h, qt, tid, hf, valid ? l1 * inv : 0.f, valid ? l2 * inv : 0.f);
     } else {
       // a piece that starts at the span's first iteration uses the span's slot 0, a later one slot 1
-      float *slot = p.slots + (int64_t(2 * span + (piece_pos == span_lo ? 0 : 1))) * Slot<D>::kFloats;
+      float *slot = p.slots + slot_index(p, span, piece_pos == span_lo ? 0 : 1, qt) * Slot<D>::kFloats;
       float4 st = {m, lt, l1, l2};
       *reinterpret_cast<float4 *>(Slot<D>::stats(slot, tid)) = st;
       if (!SCORE_ONLY) {
@@ -586,6 +601,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
           }
       }
     }
+  }
   }
 }
 
@@ -611,13 +627,13 @@ __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParam
     unit -= p.n_qtiles;
   }
   const int qt = unit;
-  const int u_lo = p.cum[hh] + qt * n_tiles, u_hi = u_lo + n_tiles;
-  // spans that hold the first and the last iteration of the unit
-  int s_lo = int((int64_t(u_lo) * p.n_wg) / p.total_iters);
-  while (span_begin(s_lo + 1, p.total_iters, p.n_wg) <= u_lo) ++s_lo;
-  while (span_begin(s_lo, p.total_iters, p.n_wg) > u_lo) --s_lo;
+  const int u_lo = p.cum[hh], u_hi = u_lo + n_tiles;
+  // spans that hold the first and the last column of the head
+  int s_lo = int((int64_t(u_lo) * p.n_teams) / p.total_cols);
+  while (span_begin(s_lo + 1, p.total_cols, p.n_teams) <= u_lo) ++s_lo;
+  while (span_begin(s_lo, p.total_cols, p.n_teams) > u_lo) --s_lo;
   int s_hi = s_lo;
-  while (span_begin(s_hi + 1, p.total_iters, p.n_wg) < u_hi) ++s_hi;
+  while (span_begin(s_hi + 1, p.total_cols, p.n_teams) < u_hi) ++s_hi;
   if (s_lo == s_hi) return;                       // the unit was finished in place
 
   float M = -INFINITY, Lt = 0.f, La = 0.f, Lb = 0.f;
@@ -628,9 +644,9 @@ __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParam
     for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
 #pragma unroll 1
   for (int sp = s_lo; sp <= s_hi; ++sp) {
-    const int b = span_begin(sp, p.total_iters, p.n_wg);
+    const int b = span_begin(sp, p.total_cols, p.n_teams);
     const int piece_lo = max(u_lo, b);
-    const float *slot = p.slots + (int64_t(2 * sp + (piece_lo == b ? 0 : 1))) * Slot<D>::kFloats;
+    const float *slot = p.slots + slot_index(p, sp, piece_lo == b ? 0 : 1, qt) * Slot<D>::kFloats;
     const float4 st = *reinterpret_cast<const float4 *>(Slot<D>::stats(const_cast<float *>(slot), tid));
     const float m_new = fmaxf(M, st.x);
     const float w_old = fast_exp2((M - m_new) * p.c), w_new = fast_exp2((st.x - m_new) * p.c);
@@ -677,7 +693,7 @@ __global__ void df_score_finish_kernel(const float *part, float *score, int n_qt
   score[3 * h + 2] = (float(n_rows) - b) * inv;
 }
 
-constexpr int64_t kMaxBufferBytes = 0x7ffff000;   // one head's rows must stay below the "no tile" offset
+constexpr int64_t kMaxBufferBytes = 0x7ff00000;   // one head's rows must stay below the "no tile" offset
 constexpr int kMinQTile = 128;   // smallest query tile any kernel variant uses (sizes the workspace)
 
 // Workspace layout: [score partials: H * ceil(Nq/128) * 4 floats, rounded up to 256 B]
@@ -690,32 +706,38 @@ static size_t slot_bytes(int d) {
   return size_t(d == 128 ? Slot<128>::kFloats : Slot<64>::kFloats) * sizeof(float);
 }
 static size_t workspace_bytes(int H, int d, int Nq) {
-  return part_bytes(H, Nq) + 2 * size_t(kNumCU) * slot_bytes(d);
+  // two slots per (team, query tile of a pass); teams * team size <= kNumCU
+  const size_t n_qtiles = (size_t(Nq) + kBQ - 1) / kBQ;
+  const size_t rounds = (n_qtiles + kNumCU - 1) / kNumCU;
+  return part_bytes(H, Nq) + 2 * size_t(kNumCU) * rounds * slot_bytes(d);
 }
 
 template <int D, bool SCORE_ONLY>
 static df_status launch(AttnParams &p, void *workspace, float *score_out, hipStream_t st) {
   p.n_qtiles = (p.Nq + kBQ - 1) / kBQ;
   p.n_units = p.n_qtiles * p.H;
-  // the line of tile iterations: heads longest first, query tiles of a head next to each other
+  // the line of columns: key tiles of all heads, longest head first
   int64_t total = 0;
   for (int hh = 0; hh < p.H; ++hh) {
     const int h = p.order[hh];
     const int64_t len = p.hist_off[h + 1] - p.hist_off[h];
     const int64_t sink = p.sink_len[h];
-    const int64_t nt = (sink + kKT - 1) / kKT + (len - sink + kKT - 1) / kKT + (p.Nc + kKT - 1) / kKT;
     p.cum[hh] = int32_t(total);
-    total += nt * p.n_qtiles;
+    total += (sink + kKT - 1) / kKT + (len - sink + kKT - 1) / kKT + (p.Nc + kKT - 1) / kKT;
     if (total > INT32_MAX / 2) return DF_ERR_RANGE;
   }
   p.cum[p.H] = int32_t(total);
-  p.total_iters = int32_t(total);
-  p.n_wg = int32_t(std::max<int64_t>(1, std::min<int64_t>(kNumCU, total / kMinSpan)));
+  p.total_cols = int32_t(total);
+  p.team_size = std::min(p.n_qtiles, kNumCU);
+  p.rounds = (p.n_qtiles + p.team_size - 1) / p.team_size;
+  p.n_teams = int32_t(std::max<int64_t>(1, std::min<int64_t>(kNumCU / p.team_size, total / kMinSpan)));
   p.part = score_out ? static_cast<float *>(workspace) : nullptr;
   p.slots = reinterpret_cast<float *>(static_cast<char *>(workspace) + part_bytes(p.H, p.Nq));
-  hipLaunchKernelGGL((df_attn_kernel<D, SCORE_ONLY>), dim3(p.n_wg), dim3(kThreads), 0, st, p);
+  const int n_wg = p.n_teams * p.team_size;
+  const int grid = n_wg >= kXcd ? (n_wg + kXcd - 1) / kXcd * kXcd : n_wg;   // XCD-major numbering needs a multiple of 8
+  hipLaunchKernelGGL((df_attn_kernel<D, SCORE_ONLY>), dim3(grid), dim3(kThreads), 0, st, p);
   if (df_status s = launch_status()) return s;
-  if (p.n_wg > 1) {
+  if (p.n_teams > 1) {
     hipLaunchKernelGGL((df_attn_merge_kernel<D, SCORE_ONLY>), dim3(p.n_units), dim3(kThreads), 0, st, p);
     if (df_status s = launch_status()) return s;
   }
@@ -795,7 +817,8 @@ extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
   p.q_st = a->q_stride_tok; p.q_sh = a->q_stride_head;
   p.kc_st = a->kc_stride_tok; p.kc_sh = a->kc_stride_head;
   p.o_st = a->o_stride_tok; p.o_sh = a->o_stride_head;
-  if ((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2 >= kMaxBufferBytes) return DF_ERR_RANGE;
+  if ((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2 >= kMaxBufferBytes || a->kc_stride_tok >= (1 << 24))
+    return DF_ERR_RANGE;
   p.cur_bytes = uint32_t((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2);
   p.scale = a->softmax_scale;
   p.c = a->softmax_scale * 1.4426950408889634f;
@@ -834,7 +857,8 @@ extern "C" df_status df_head_score(const df_score_args *a, void *stream) {
   p.out = nullptr;
   p.lse = nullptr;
   p.kc_st = a->kc_stride_tok; p.kc_sh = a->kc_stride_head;
-  if ((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2 >= kMaxBufferBytes) return DF_ERR_RANGE;
+  if ((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2 >= kMaxBufferBytes || a->kc_stride_tok >= (1 << 24))
+    return DF_ERR_RANGE;
   p.cur_bytes = uint32_t((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2);
   p.scale = a->softmax_scale;
   p.c = a->softmax_scale * 1.4426950408889634f;
