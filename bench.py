@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, datasheet
 
 # HBM bytes per attention launch from rocprofv3 --pmc runs (FETCH_SIZE / WRITE_SIZE scaled by a
 # copy kernel of known size); see profiles/.  None = not measured for that workload yet.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"config2_wan1.3b_480p": 268.7e6}   # profiles/config2_hot_path_rocprofv3.md
 
 
 def _blas_threads() -> int:
@@ -191,7 +191,7 @@ def main():
                    "keys_per_head": [w.visible_len(h) + w.Nc for h in range(H)],
                    "dummy_heads": n_dummy, "step": "head_score+classify, pack+attn(fused score)+append",
                    "classified_dummy": [h for h, t in enumerate(types) if t == df.DF_HEAD_DUMMY]},
-        "roofline": {"bound": "mfma", "kernel": "df_attn_kernel", "achieved": round(attn_tflops, 2),
+        "roofline": {"bound": "mfma", "kernel": "df_attn_fwd = df_attn_kernel + df_attn_merge_kernel + df_score_finish_kernel", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "flop_per_launch": attn_flop,
                      "ms_per_launch": round(per["attn"], 4)},
