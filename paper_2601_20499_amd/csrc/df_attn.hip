@@ -50,7 +50,7 @@
 // l in fp32.  The maximum is only raised (and O, l rescaled) when some row of
 // the wave exceeds it by more than 2^8, which keeps P within bf16/fp32 range
 // and makes rescaling rare; P is rounded to bf16 (RNE) before the second
-// product and l sums the rounded values (v_dot2 with ones).  The output is divided by l and
+// product; l sums the unrounded fp32 values.  The output is divided by l and
 // rounded to bf16 once at the end.
 //
 // The frame attention score of Eq. 3 falls out of the same statistics: with the
@@ -343,6 +343,8 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   const int voff_hist = dma_pos * L::NG * L::ROWB + dma_chunk;
   const int voff_cur = dma_pos * L::NG * int(cur_stride_b) + dma_chunk;
   constexpr uint32_t kNoTile = 0x7ff00000u;      // beyond every descriptor (plus any lane offset): the load writes zeros
+  const uint32_t lane_vo_hist = uint32_t(voff_hist) + uint32_t(wave) * L::ROWB;      // lane offset + this wave's first row group
+  const uint32_t lane_vo_cur = uint32_t(voff_cur) + uint32_t(wave) * cur_stride_b;
 
 #pragma unroll 1
   for (int round = 0; round < p.rounds; ++round) {
@@ -402,6 +404,47 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
       }
     };
 
+    // Inside the tile loop the loads follow two cursors (K three tiles ahead, V two), advanced by one
+    // tile per iteration: byte offset += keys per tile * row stride, except at the few tiles where a
+    // cursor enters the window region, the current chunk or the end of the piece.  That keeps the
+    // scalar work per iteration to a handful of instructions.
+    struct Cursor { int t; uint32_t toff; uint32_t step; int next_event; bool cur; };
+    auto locate = [&](int t) {
+      Cursor c;
+      c.t = t;
+      c.cur = false;
+      if (t >= t_end) { c.toff = kNoTile; c.step = 0; c.next_event = INT32_MAX; }
+      else if (t < nt0) { c.toff = uint32_t(t * kKT) * L::ROWB; c.step = kKT * L::ROWB; c.next_event = min(nt0, t_end); }
+      else if (t < nt0 + nt1) {
+        c.toff = uint32_t(sink + (t - nt0) * kKT) * L::ROWB; c.step = kKT * L::ROWB; c.next_event = min(nt0 + nt1, t_end);
+      } else {
+        c.cur = true; c.toff = uint32_t((t - nt0 - nt1) * kKT) * cur_stride_b; c.step = kKT * cur_stride_b; c.next_event = t_end;
+      }
+      return c;
+    };
+    auto advance = [&](Cursor &c) {
+      ++c.t;
+      c.toff += c.step;
+      if (c.t == c.next_event) c = locate(c.t);
+    };
+    // this wave's share of the tile under cursor c into the LDS tile at byte address dst
+    auto dma_cursor = [&](const Cursor &c, unsigned dst, bool is_v) {
+      const int gs = is_v ? L::VGS : L::KGS;
+      if (c.cur) {
+        const uint32_t vo = lane_vo_cur + c.toff;
+#pragma unroll
+        for (int i = 0; i < GPW; ++i)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vc : rs_kc, (lds_void *)(uintptr_t)(dst + (wave + kWaves * i) * gs),
+                                                   16, int(vo + uint32_t(kWaves * i) * cur_stride_b), 0, 0, 0);
+      } else {
+        const uint32_t vo = lane_vo_hist + c.toff;
+#pragma unroll
+        for (int i = 0; i < GPW; ++i)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vh : rs_kh, (lds_void *)(uintptr_t)(dst + (wave + kWaves * i) * gs),
+                                                   16, int(vo + uint32_t(kWaves * i) * L::ROWB), 0, 0, 0);
+      }
+    };
+
     // ---- Q fragment: B operand of S^T = K Q^T.  Lane (j, hf) holds, for query j,
     // elements 16*ks + 8*hf .. +7 of every k-step.
     bf16x8 qf[KS];
@@ -447,6 +490,20 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) pb[kb][ts][e] = (__bf16)0.f;
     int k_slot = 0, v_slot = kNBuf - 1;      // LDS buffer of K(t) and of V(t-1)
+    Cursor kc = locate(t_begin + 2), vc = locate(t_begin + 1);   // the last tiles the prologue has issued
+    unsigned kd_slot = 2, vd_slot = 1;                           // and their LDS buffers
+    // every wave issues the same number of loads once per VALU phase (absent tiles load zeros), so
+    // the s_waitcnt count at the end of the MFMA phase holds
+    auto phase_loads = [&]() {
+      advance(kc);
+      kd_slot = (kd_slot + 1) % kNBuf;
+      dma_cursor(kc, lds_address(lds_k) + kd_slot * L::KTILE, false);
+      if (!SCORE_ONLY) {
+        advance(vc);
+        vd_slot = (vd_slot + 1) % kNBuf;
+        dma_cursor(vc, lds_address(lds_v) + vd_slot * L::VTILE, true);
+      }
+    };
 
     const int seg_end0 = nt0 - 1, seg_end1 = nt0 + nt1 - 1;
     float mx = 0.f, mx4[4] = {0.f, 0.f, 0.f, 0.f};
@@ -507,9 +564,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDmaPerPhase) : "memory");
       lds_barrier();
       // ================= VALU / memory phase =================
-      // always the same number of loads per phase (absent tiles load zeros), so the count above holds
-      dma_tile(t + 3, (t + 3 - t_begin) % kNBuf, false);
-      if (!SCORE_ONLY) dma_tile(t + 2, (t + 2 - t_begin) % kNBuf, true);
+      phase_loads();
       if (t < t_end) {
         if (SCORE_ONLY) {                     // no second product to hide behind: reduce here
           if (n_valid_t < kKT) {
@@ -543,7 +598,6 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
           }
         }
         const float nmc = -m * p.c;
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -554,7 +608,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
               const float e0 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e], p.c, nmc));
               const float e1 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e + 1], p.c, nmc));
               w[e] = pack_bf16x2(e0, e1);
-              l4[e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e]), ones, l4[e], false);
+              l4[e] += e0 + e1;     // plain adds: the dot-product instructions share the matrix core and stall its MFMAs
             }
             u32x4 u = {w[0], w[1], w[2], w[3]};
             pb[kb][ts] = __builtin_bit_cast(bf16x8, u);
