@@ -30,10 +30,12 @@
 // Schedule.  The 8 waves form two groups of 4 (one wave of each group per
 // SIMD).  Every tile iteration of a wave has an MFMA phase (S = K Q^T of tile t
 // and O += V^T P^T of tile t-1) and a VALU/memory phase (online softmax of tile
-// t, LDS stores of the staged tile, global loads of a later tile), separated
-// by workgroup barriers.  Group 1 starts one barrier late, so on every SIMD one
-// wave is in its MFMA phase while the other is in its VALU phase: the matrix
-// core and the vector ALU overlap without relying on instruction scheduling.
+// t, issue of the global loads of a later tile).  The workgroup meets at one
+// barrier per iteration, which group 0 takes after its VALU phase and group 1
+// after its MFMA phase: between two barriers group 0 runs MFMA(t), VALU(t) and
+// group 1 runs VALU(t-1), MFMA(t), so on every SIMD one wave is in its MFMA
+// phase while the other is in its VALU phase: the matrix core and the vector
+// ALU overlap without relying on instruction scheduling.
 //
 // Staging.  K and V tiles go from global memory straight into LDS with
 // buffer_load_dwordx4 ... lds (no registers, no LDS store instructions); rows
@@ -471,7 +473,6 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();
-    if (group == 1) lds_barrier();          // stagger: group 1 runs one phase behind group 0
 
     f32x16 o[DB];
 #pragma unroll
@@ -559,10 +560,17 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
         k_slot = (k_slot == kNBuf - 1) ? 0 : k_slot + 1;   // slot of K(t+1)
         v_slot = (v_slot == kNBuf - 1) ? 0 : v_slot + 1;   // slot of V(t)
       }
-      // the loads of the VALU phase before last (tiles K(t+1), V(t)) must have landed before this
-      // barrier; the latest phase's loads may stay in flight
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDmaPerPhase) : "memory");
-      lds_barrier();
+      // One workgroup barrier per iteration, taken by group 1 here and by group 0 after its VALU
+      // phase: between two barriers group 0 runs MFMA(t), VALU(t) and group 1 runs VALU(t-1), MFMA(t),
+      // so the two waves of a SIMD are in opposite phases without being locked phase by phase.
+      // Before the barrier a wave makes sure that its loads of all but the latest VALU phase have
+      // landed (tiles up to K(t+2), V(t+1)); behind it every wave has finished MFMA(t-1), whose
+      // tiles' buffers the next VALU phases overwrite.
+      auto iteration_barrier = [&]() {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDmaPerPhase) : "memory");
+        lds_barrier();
+      };
+      if (group == 1) iteration_barrier();
       // ================= VALU / memory phase =================
       phase_loads();
       if (t < t_end) {
@@ -613,13 +621,17 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
             u32x4 u = {w[0], w[1], w[2], w[3]};
             pb[kb][ts] = __builtin_bit_cast(bf16x8, u);
           }
-        if (t == seg_end0) { snap_m0 = m; snap_l0 = (l4[0] + l4[1]) + (l4[2] + l4[3]); }
-        if (t == seg_end1) { snap_m1 = m; snap_l1 = (l4[0] + l4[1]) + (l4[2] + l4[3]); }
+        if (t == seg_end0 || t == seg_end1) {  // rare: keep the bookkeeping out of the common path
+          const float lsum = (l4[0] + l4[1]) + (l4[2] + l4[3]);
+          if (t == seg_end0) { snap_m0 = m; snap_l0 = lsum; }
+          if (t == seg_end1) { snap_m1 = m; snap_l1 = lsum; }
+        }
       }
-      lds_barrier();
+      if (group == 0) iteration_barrier();
     }
-    if (group == 0) lds_barrier();          // matches group 1's extra barrier at the start
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no load of this piece may land in the next one's tiles
+    // no load of this piece may land in the next one's tiles, and no wave may still be reading them
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
     // Region sums of this piece: a region that ended before the piece began contributes nothing, a
     // region the piece ends in (or before) contains everything the piece has summed.
     const float l_piece = (l4[0] + l4[1]) + (l4[2] + l4[3]);
