@@ -51,7 +51,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config4", "config5"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config4", "config5", "dhp3"],
+                    help="config2 is the headline workload; dhp3 = the paper's full method on the same geometry "
+                         "(sink / neighbour / packed dummy heads from Dynamic Head Programming, half of the heads dummy)")
+    ap.add_argument("--layer", type=int, default=3, help="layer of the seeded 30-layer stack (dhp3 only)")
+    ap.add_argument("--variants", action="store_true",
+                    help="dhp3 only: also time df_attn_fwd under the ablation's other head typings (Tab. 6) and dense")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="oracle rows per head (0 = sized for ~15 s)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
@@ -120,10 +125,33 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    w = getattr(wl, args.workload)()
+    mode = df.DF_CLASSIFY_TWO_CLASS
+    if args.workload == "dhp3":
+        # head types are not given: they come out of the scores (Dynamic Head Programming, Eq. 6-7)
+        mode = df.DF_CLASSIFY_DHP
+        w = wl.dhp3_layer(args.layer)
+        kp, _, off0, sl0 = wl.packed_history(w)
+        F0 = torch.empty(w.H, 3, dtype=torch.float32, device=dev)
+        ws0 = torch.empty(df.df_attn_workspace_bytes(w.H, w.d, w.Nq), dtype=torch.uint8, device=dev)
+        df.df_head_score(w.q.to(dev), w.k_cur.to(dev), kp.to(dev), off0, sl0, F0, w.scale,
+                         q_sample_stride=4, q_offset=0, workspace=ws0)
+        base_types, _ = df.df_classify(F0.cpu().tolist(), w.H // 2, mode)
+        del kp, F0, ws0
+
+        def typed(types):
+            import copy
+            v = copy.copy(w)
+            v.head_type, v.n_sink, v.n_win = list(types), [0] * w.H, [0] * w.H
+            for h, t in enumerate(types):
+                v.n_sink[h], v.n_win[h] = df.df_head_context(t, w.T, w.sink_frames, w.hist_frames - w.sink_frames)
+            return v
+        packed = [df.DF_HEAD_PACK_DUMMY if t == df.DF_HEAD_DUMMY else t for t in base_types]
+        w = typed(packed)                      # dummy heads keep one packing frame (Eq. 8)
+    else:
+        w = getattr(wl, args.workload)()
     st = build_state(w, df, torch, dev)
     H = w.H
-    n_dummy = sum(1 for t in w.head_type if t == wl.HEAD_DUMMY)
+    n_dummy = sum(1 for t in w.head_type if t in (wl.HEAD_DUMMY, wl.HEAD_PACK_DUMMY))
     K, W = args.steps, args.warmup
     F_host = [torch.empty(H, 3, dtype=torch.float32).pin_memory() for _ in range(K + W)]
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -165,7 +193,7 @@ def main():
     torch.cuda.synchronize()
     types = None
     for i in range(W, W + K):          # host part of the step: classification of the copied scores
-        types, _ = df.df_classify(F_host[i].tolist(), n_dummy, df.DF_CLASSIFY_TWO_CLASS)
+        types, _ = df.df_classify(F_host[i].tolist(), n_dummy, mode)
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / K
 
@@ -173,8 +201,10 @@ def main():
            for j, n in enumerate(names)}
     attn_flop = w.attn_flop()
     score_flop = w.score_flop(4)
-    designated = [h for h, t in enumerate(w.head_type) if t == wl.HEAD_DUMMY]
+    designated = [h for h, t in enumerate(w.head_type) if t in (wl.HEAD_DUMMY, wl.HEAD_PACK_DUMMY)]
     assert [h for h, t in enumerate(types) if t == df.DF_HEAD_DUMMY] == designated, (types, designated)
+    if args.workload == "dhp3":
+        assert list(types) == list(base_types), (types, base_types)
     value = (attn_flop + score_flop) / (ms_step * 1e-3) / 1e12
     attn_tflops = attn_flop / (per["attn"] * 1e-3) / 1e12
     pack_bytes = 2 * 2 * sum(w.visible_len(h) for h in range(H)) * w.d * 2
@@ -202,6 +232,43 @@ def main():
         "pack_frac_hbm": round(pack_bytes / (per["pack"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if pack_bytes else None,
         "paper_context": "H100 end-to-end only: up to 2.0x speedup, 24.3 FPS, 17.6->19.6 FPS from pruning 25% of heads",
     }
+
+    if args.workload == "dhp3":
+        result["config"]["head_types"] = list(w.head_type)
+        result["config"]["planted_roles"] = list(w.roles)
+    if args.workload == "dhp3" and args.variants:
+        # the same layer under other head typings: attention alone, history packed on the host
+        D, S, NB, PK, FU = df.DF_HEAD_DUMMY, df.DF_HEAD_SINK, df.DF_HEAD_NEIGHBOR, df.DF_HEAD_PACK_DUMMY, df.DF_HEAD_FULL
+        dummy = [t == D for t in base_types]
+        variants = {
+            "dense_all_full": [FU] * H,
+            "two_class_full_plus_dummy": [D if x else FU for x in dummy],
+            "two_class_full_plus_packed_dummy": [PK if x else FU for x in dummy],
+            "dhp3_no_packing_frame": list(base_types),
+            "dhp3_packed (the method)": packed,
+        }
+        res = {}
+        for name, tys in variants.items():
+            v = typed(tys)
+            kp, vp, off, sl = wl.packed_history(v)
+            kp, vp = kp.to(dev), vp.to(dev)
+            for _ in range(3):
+                df.df_attn_fwd(st["q"], st["k_cur"], st["v_cur"], kp, vp, off, sl, st["out"], w.scale, workspace=st["ws"])
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(20):
+                df.df_attn_fwd(st["q"], st["k_cur"], st["v_cur"], kp, vp, off, sl, st["out"], w.scale, workspace=st["ws"])
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 20
+            res[name] = {"attn_ms": round(ms, 4), "GFLOP": round(v.attn_flop() / 1e9, 1),
+                         "TFLOPs": round(v.attn_flop() / ms / 1e9, 1),
+                         "cached_frames_per_head": round(sum(v.visible_len(h) for h in range(H)) / H / w.T, 3)}
+            del kp, vp
+        dense = res["dense_all_full"]["attn_ms"]
+        for r in res.values():
+            r["speedup_vs_dense"] = round(dense / r["attn_ms"], 3)
+        result["variants"] = res
 
     if not args.no_cpu_baseline:
         import numpy as np

@@ -41,6 +41,7 @@ class Workload:
     n_sink: List[int]           # visible sink tokens per head
     n_win: List[int]            # visible window tokens per head
     planted: List[int] = field(default_factory=list)   # heads biased towards the current chunk
+    roles: List[str] = field(default_factory=list)     # planted role per head, where a generator sets one
     q: Optional[torch.Tensor] = None        # [Nq, H, d] bf16
     k_cur: Optional[torch.Tensor] = None    # [Nc, H, d] bf16
     v_cur: Optional[torch.Tensor] = None
@@ -96,9 +97,10 @@ def _gauss(gen, shape, std=1.0, dtype=torch.float32):
 
 
 def _draw(w: Workload, planted: List[int], bias: float = 2.0, weak_bias: Optional[List[float]] = None,
-          q_mean_std: float = 0.4, fp32: bool = False):
+          q_mean_std: float = 0.4, fp32: bool = False, sink_bias: Optional[List[float]] = None):
     """Q = G + mu_h with mu_h ~ q_mean_std * N(0, I); K, V element-wise N(0,1).
-    Planted heads get K_cur += bias * mean_u(Q_h); other heads optionally a weak bias."""
+    Planted heads get K_cur += bias * mean_u(Q_h); other heads optionally a weak bias.
+    sink_bias[h] != 0 shifts the keys of head h's sink frame(s) the same way (a sink-focused head)."""
     g = torch.Generator().manual_seed(w.seed)
     H, d = w.H, w.d
     dt = torch.float32
@@ -114,7 +116,15 @@ def _draw(w: Workload, planted: List[int], bias: float = 2.0, weak_bias: Optiona
             k_cur[:, h, :] += b * q_mean[h]
     store = torch.float32 if fp32 else torch.bfloat16
     w.q, w.k_cur, w.v_cur = q.to(store), k_cur.to(store), v_cur.to(store)
-    w.k_hist = _gauss(g, (w.Nh, H, d), dtype=store)
+    if sink_bias is None:
+        w.k_hist = _gauss(g, (w.Nh, H, d), dtype=store)
+    else:
+        k_hist = _gauss(g, (w.Nh, H, d), dtype=dt)
+        ns = min(w.sink_frames * w.T, w.Nh)
+        for h in range(H):
+            if sink_bias[h] != 0.0:
+                k_hist[:ns, h, :] += sink_bias[h] * q_mean[h]
+        w.k_hist = k_hist.to(store)
     w.v_hist = _gauss(g, (w.Nh, H, d), dtype=store)
     w.planted = list(planted)
     return w
@@ -179,6 +189,35 @@ def config5(T: int = 1560, hist_frames: int = 60) -> Workload:
         w.n_sink[h] = T
         w.n_win[h] = (f - 1) * T
     return _draw(w, planted=dummy)
+
+
+def dhp3_layer(layer: int, T: int = 1560, hist_frames: int = 6, d: int = 128, H: int = 12) -> Workload:
+    """One layer of a 30-layer stack for the paper's full method (Sec. 3.3: sink / neighbour /
+    dummy heads, half of all heads dummy, classified globally over all layers' heads): config-2
+    geometry (1 sink + hist_frames-1 recent frames, 3-frame chunk); every head gets a seeded role
+    and strength: about half lean on the current chunk, about a fifth on the sink frame, the others
+    keep the spread-out profile of plain Gaussians (most mass on the recent frames).  Head types are
+    left FULL: they come from the classification under test.  `roles[h]` in {"current", "sink",
+    "neighbor"} records what was planted."""
+    g = torch.Generator().manual_seed(5000 + layer)
+    u = torch.rand(H, generator=g).tolist()
+    strength = torch.rand(H, generator=g).tolist()
+    cur_bias, snk_bias, roles = [0.0] * H, [0.0] * H, []
+    for h in range(H):
+        if u[h] < 0.5:
+            roles.append("current")
+            cur_bias[h] = 1.0 + 1.5 * strength[h]
+        elif u[h] < 0.7:
+            roles.append("sink")
+            snk_bias[h] = 1.5 + 1.5 * strength[h]
+        else:
+            roles.append("neighbor")
+            cur_bias[h] = 0.4 * strength[h]
+    w = _typed(f"dhp3_layer{layer}_T{T}", H, d, T, 3, hist_frames, [HEAD_FULL] * H, seed=7000 + layer)
+    _draw(w, planted=[], weak_bias=cur_bias, sink_bias=snk_bias)
+    w.planted = [h for h in range(H) if roles[h] == "current"]
+    w.roles = roles
+    return w
 
 
 def small_ragged(seed: int, H: int = 3, d: int = 128, T: int = 37, chunk_frames: int = 3,
