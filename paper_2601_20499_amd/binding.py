@@ -242,3 +242,39 @@ def df_pack_context(cache: Cache, take_sink, take_win, k_out, v_out, stream=None
     a.hist_off_out, a.sink_len_out = off, sl
     _check(lib.df_pack_context(C.byref(a), _stream_handle(stream)), "df_pack_context")
     return list(off), list(sl)
+
+
+def prepared_pack(cache: Cache, take_sink, take_win, k_out, v_out, stream=None):
+    """df_pack_context with the arguments marshalled once: returns a function that issues the call.
+    For loops in which the Python-side marshalling would otherwise be the slower part."""
+    a = df_pack_args()
+    a.cache = C.pointer(cache.c)
+    ts, tw = _i32(take_sink), _i32(take_win)
+    a.take_sink, a.take_win = ts, tw
+    a.k_out, a.v_out = _ptr(k_out), _ptr(v_out)
+    a.out_capacity_rows = k_out.shape[0]
+    off = (C.c_int64 * (cache.H + 1))()
+    sl = (C.c_int32 * cache.H)()
+    a.hist_off_out, a.sink_len_out = off, sl
+    keep = (a, ts, tw, off, sl, k_out, v_out, cache)
+    handle = _stream_handle(stream)
+
+    def call(_keep=keep):
+        _check(lib.df_pack_context(C.byref(a), handle), "df_pack_context")
+    return call
+
+
+def prepared_append(cache: Cache, k_new, v_new, stream=None):
+    """df_kv_append with the arguments marshalled once (the cache state still advances per call)."""
+    a = df_append_args()
+    a.cache = C.pointer(cache.c)
+    a.k_new, a.v_new = _ptr(k_new), _ptr(v_new)
+    a.stride_tok, a.stride_head = k_new.stride(0), k_new.stride(1)
+    assert v_new.stride() == k_new.stride()
+    a.Nc = k_new.shape[0]
+    keep = (a, k_new, v_new, cache)
+    handle = _stream_handle(stream)
+
+    def call(_keep=keep):
+        _check(lib.df_kv_append(C.byref(a), handle), "df_kv_append")
+    return call

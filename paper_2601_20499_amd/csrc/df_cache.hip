@@ -39,12 +39,13 @@ struct CopyParams {
 };
 
 constexpr int kCopyThreads = 256;
-constexpr int kVecPerBlock = 1024;     // 16-byte vectors per workgroup: 4 per thread, 64 rows of d = 128
+constexpr int kVecPerBlock = 512;      // 16-byte vectors per workgroup: 2 per thread, 32 rows of d = 128
 
-template <bool APPEND>
+// RV = 16-byte vectors per row (d / 8), a template parameter so that row/column come from shifts
+template <bool APPEND, int RV>
 __global__ __launch_bounds__(kCopyThreads) void df_rows_kernel(const CopyParams p) {
   const HeadPlan &pl = p.plan[blockIdx.y];
-  const int rv = p.row_vec;
+  constexpr int rv = RV;
   const int n_vec = (pl.n_a + pl.n_b) * rv;
   const int v0 = blockIdx.x * kVecPerBlock + threadIdx.x;
   if (blockIdx.x * kVecPerBlock >= n_vec) return;
@@ -78,7 +79,8 @@ __global__ __launch_bounds__(kCopyThreads) void df_rows_kernel(const CopyParams 
   }
 #pragma unroll
   for (int it = 0; it < kPer; ++it)
-    if (daddr[it] >= 0) dst[daddr[it]] = val[it];
+    // written once and not read again by this kernel: non-temporal stores leave the cache to the reads
+    if (daddr[it] >= 0) __builtin_nontemporal_store(val[it], &dst[daddr[it]]);
 }
 
 static df_status check_cache(const df_cache *c) {
@@ -155,7 +157,10 @@ extern "C" df_status df_kv_append(const df_append_args *a, void *stream) {
   p.n_plans = np;
   if (np > 0) {
     dim3 grid((max_rows * p.row_vec + kVecPerBlock - 1) / kVecPerBlock, np, 2);
-    hipLaunchKernelGGL(df_rows_kernel<true>, grid, dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream), p);
+    if (p.row_vec == 16)
+      hipLaunchKernelGGL((df_rows_kernel<true, 16>), grid, dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream), p);
+    else
+      hipLaunchKernelGGL((df_rows_kernel<true, 8>), grid, dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream), p);
     if (df_status s = launch_status()) return s;
   }
   for (int h = 0; h < c->H; ++h) {
@@ -211,7 +216,10 @@ extern "C" df_status df_pack_context(const df_pack_args *a, void *stream) {
   p.n_plans = np;
   if (np > 0) {
     dim3 grid((max_rows * p.row_vec + kVecPerBlock - 1) / kVecPerBlock, np, 2);
-    hipLaunchKernelGGL(df_rows_kernel<false>, grid, dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream), p);
+    if (p.row_vec == 16)
+      hipLaunchKernelGGL((df_rows_kernel<false, 16>), grid, dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream), p);
+    else
+      hipLaunchKernelGGL((df_rows_kernel<false, 8>), grid, dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream), p);
     if (df_status s = launch_status()) return s;
   }
   for (int h = 0; h <= c->H; ++h) a->hist_off_out[h] = off[h];
