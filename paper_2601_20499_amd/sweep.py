@@ -1,0 +1,84 @@
+"""Single-layer attention time against context length and against the number of dummy heads
+(the two per-layer curves of the paper: runtime vs context length, and vs the dummy-head count),
+dense sliding-window attention against the head-heterogeneous contexts, on the same kernel.
+
+    python -m paper_2601_20499_amd.sweep [--T 1560] [--reps 20]
+
+Random bf16 tensors of the Wan-1.3B layer geometry (12 heads x 128, 3-frame chunk); only shapes
+matter for the time.  Prints two markdown tables.
+"""
+from __future__ import annotations
+
+import argparse
+
+import torch
+
+from . import binding as df
+
+H, D, CHUNK = 12, 128, 3
+
+
+def time_attn(T, frames_per_head, sink_frames_per_head, reps, dev):
+    """frames_per_head[h] = history frames head h sees; returns (ms, GFLOP)."""
+    Nq = CHUNK * T
+    lens = [f * T for f in frames_per_head]
+    off = [0]
+    for n in lens:
+        off.append(off[-1] + n)
+    sl = [min(s * T, n) for s, n in zip(sink_frames_per_head, lens)]
+    g = torch.Generator(device=dev).manual_seed(0)
+    mk = lambda *shape: torch.randn(*shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q, kc, vc = mk(Nq, H, D), mk(Nq, H, D), mk(Nq, H, D)
+    kh, vh = mk(max(off[-1], 1), D), mk(max(off[-1], 1), D)
+    out = torch.empty_like(q)
+    ws = torch.empty(df.df_attn_workspace_bytes(H, D, Nq), dtype=torch.uint8, device=dev)
+    call = lambda: df.df_attn_fwd(q, kc, vc, kh, vh, off, sl, out, D ** -0.5, workspace=ws)
+    for _ in range(3):
+        call()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    flop = sum(4.0 * Nq * (n + Nq) * D for n in lens)
+    return e0.elapsed_time(e1) / reps, flop / 1e9
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--T", type=int, default=1560, help="tokens per latent frame")
+    ap.add_argument("--reps", type=int, default=20)
+    a = ap.parse_args()
+    assert torch.cuda.is_available(), "needs a GPU"
+    dev = torch.device("cuda:0")
+
+    print(f"### attention ms per chunk-layer vs cached frames (T = {a.T}, 12 heads, 3-frame chunk)")
+    print("| cached frames L (1 sink + L-1 recent) | dense ms | TFLOP/s | 6 packed dummy + 2 sink + 4 neighbour ms | TFLOP/s | speedup |")
+    print("|---|---|---|---|---|---|")
+    for L in (3, 6, 9, 12, 15, 21, 30):
+        dense_ms, dense_gf = time_attn(a.T, [L] * H, [1] * H, a.reps, dev)
+        frames = [1] * 6 + [1] * 2 + [L - 1] * 4            # packing frame | sink frame | L-1 recent frames
+        sinks = [0] * 6 + [1] * 2 + [0] * 4
+        m_ms, m_gf = time_attn(a.T, frames, sinks, a.reps, dev)
+        print(f"| {L} | {dense_ms:.3f} | {dense_gf / dense_ms:.0f} | {m_ms:.3f} | {m_gf / m_ms:.0f} | {dense_ms / m_ms:.2f}x |", flush=True)
+
+    print()
+    print(f"### attention ms vs number of dummy heads N (T = {a.T}, 1 sink + 5 recent frames cached)")
+    print("| N | full + dummy ms | speedup | full + packed dummy ms | speedup | sink/neighbour (1:2) + packed dummy ms | speedup |")
+    print("|---|---|---|---|---|---|---|")
+    L = 6
+    base_ms = None
+    for N in (0, 3, 6, 9, 12):
+        keep = H - N
+        two = time_attn(a.T, [0] * N + [L] * keep, [0] * N + [1] * keep, a.reps, dev)[0]
+        packed = time_attn(a.T, [1] * N + [L] * keep, [0] * N + [1] * keep, a.reps, dev)[0]
+        n_sink = keep // 3
+        three = time_attn(a.T, [1] * N + [1] * n_sink + [L - 1] * (keep - n_sink),
+                          [0] * N + [1] * n_sink + [0] * (keep - n_sink), a.reps, dev)[0]
+        base_ms = two if base_ms is None else base_ms
+        print(f"| {N} | {two:.3f} | {base_ms / two:.2f}x | {packed:.3f} | {base_ms / packed:.2f}x | {three:.3f} | {base_ms / three:.2f}x |", flush=True)
+
+
+if __name__ == "__main__":
+    main()
