@@ -79,6 +79,31 @@ def main():
         base_ms = two if base_ms is None else base_ms
         print(f"| {N} | {two:.3f} | {base_ms / two:.2f}x | {packed:.3f} | {base_ms / packed:.2f}x | {three:.3f} | {base_ms / three:.2f}x |", flush=True)
 
+    print()
+    print(f"### long context (T = {a.T}): sliding window of 36 frames, no window (237 frames for every head), "
+          "and 237 frames for the neighbour heads only")
+    print("| contexts of the 12 heads | cached frames / head | GFLOP | ms | TFLOP/s | vs 237-frame dense |")
+    print("|---|---|---|---|---|---|")
+    rows = [("dense, 36 frames (sliding window)", [36] * H, [1] * H),
+            ("dense, 237 frames (no window)", [237] * H, [1] * H),
+            ("6 packed dummy + 4 sink + 2 neighbour x 237 frames", [1] * 6 + [1] * 4 + [237] * 2, [0] * 6 + [1] * 4 + [0] * 2),
+            ("6 packed dummy + 2 sink + 4 neighbour x 237 frames", [1] * 6 + [1] * 2 + [237] * 4, [0] * 6 + [1] * 2 + [0] * 4)]
+    res = [(n, f, time_attn(a.T, f, sk, max(3, a.reps // 4), dev)) for n, f, sk in rows]
+    ref_ms = res[1][2][0]
+    for n, f, (ms, gf) in res:
+        print(f"| {n} | {sum(f) / H:.1f} | {gf:.0f} | {ms:.3f} | {gf / ms:.0f} | {ref_ms / ms:.2f}x |", flush=True)
+
+    print()
+    print("### 1920x1088 chunk (8160 tokens per frame, 24480 queries, 1 sink + 5 recent frames cached)")
+    print("| contexts of the 12 heads | GFLOP | ms | TFLOP/s | speedup |")
+    print("|---|---|---|---|---|")
+    rows = [("dense", [6] * H, [1] * H),
+            ("6 full + 6 packed dummy", [1] * 6 + [6] * 6, [0] * 6 + [1] * 6),
+            ("6 packed dummy + 2 sink + 4 neighbour", [1] * 6 + [1] * 2 + [5] * 4, [0] * 6 + [1] * 2 + [0] * 4)]
+    res = [(n, time_attn(8160, f, sk, max(3, a.reps // 4), dev)) for n, f, sk in rows]
+    for n, (ms, gf) in res:
+        print(f"| {n} | {gf:.0f} | {ms:.3f} | {gf / ms:.0f} | {res[0][1][0] / ms:.2f}x |", flush=True)
+
 
 if __name__ == "__main__":
     main()

@@ -220,6 +220,27 @@ def dhp3_layer(layer: int, T: int = 1560, hist_frames: int = 6, d: int = 128, H:
     return w
 
 
+def long_context_layer(window_frames: int = 237, n_neighbor: int = 2, n_sink: int = 4, T: int = 1560) -> Workload:
+    """Long-context reallocation (Sec. 4.4, the long-context table): the cache budget saved on dummy
+    and sink heads goes to the neighbour heads, which see `window_frames` past frames; the other heads
+    keep one frame (packing frame or sink).  12 heads: n_neighbor neighbour, n_sink sink, the rest
+    packed dummy; the dummy heads are the planted ones."""
+    H = 12
+    types = [HEAD_NEIGHBOR] * n_neighbor + [HEAD_SINK] * n_sink + [HEAD_PACK_DUMMY] * (H - n_neighbor - n_sink)
+    g = torch.Generator().manual_seed(11)
+    types = [types[i] for i in torch.randperm(H, generator=g).tolist()]
+    w = _typed(f"long_context_{window_frames}f", H, 128, T, 3, window_frames + 1, types, seed=12)
+    return _draw(w, planted=[h for h, t in enumerate(types) if t == HEAD_PACK_DUMMY])
+
+
+def res1080p(dummy_heads=(1, 4, 5, 8, 9, 11)) -> Workload:
+    """1920x1088 chunk (Sec. 4.3): 8160 tokens per latent frame, 24480 queries, 1 sink + 5 recent
+    frames of history, half of the heads packed dummy, the others full."""
+    types = [HEAD_PACK_DUMMY if h in dummy_heads else HEAD_FULL for h in range(12)]
+    w = _typed("res1080p", 12, 128, 8160, 3, 6, types, seed=13)
+    return _draw(w, planted=list(dummy_heads))
+
+
 def small_ragged(seed: int, H: int = 3, d: int = 128, T: int = 37, chunk_frames: int = 3,
                  hist_frames: int = 5, types=None, q_mean_std: float = 0.4, planted=()) -> Workload:
     """Small case with sizes that are multiples of no tile: used for element-wise parity."""
