@@ -99,6 +99,12 @@ typedef struct df_attn_args {
   const int64_t *hist_off;  /* HOST [H+1], hist_off[0] == 0, non-decreasing                            */
   const int32_t *hist_sink_len; /* HOST [H] or NULL: how many of head h's history rows form the sink
                                region (0 <= . <= len_h).  Required when score_out != NULL.             */
+  const int32_t *hist_len;  /* HOST [H] or NULL: len_h, the rows of head h that hold keys, counted from
+                               hist_off[h] (0 <= . <= hist_off[h+1]-hist_off[h]).  NULL = all of them.
+                               With it k_hist/v_hist may be the df_cache buffers themselves, read in
+                               place (hist_off = head_row_off, hist_sink_len = sink_len,
+                               hist_len = sink_len + win_len): a head's filled rows are a prefix of its
+                               rows, and the order of the window keys does not change the result.    */
   void *out;                /* DEVICE bf16, (u,h,c) at out[u*o_stride_tok + h*o_stride_head + c]       */
   int64_t o_stride_tok, o_stride_head;
   float *lse_out;           /* DEVICE fp32 [H, Nq] natural-log sum-exp of the scaled logits, or NULL   */
@@ -128,6 +134,7 @@ typedef struct df_score_args {
   const void *k_hist;               /* DEVICE bf16 ragged history keys, as in df_attn_args          */
   const int64_t *hist_off;          /* HOST [H+1]                                                   */
   const int32_t *hist_sink_len;     /* HOST [H], required                                           */
+  const int32_t *hist_len;          /* HOST [H] or NULL, as in df_attn_args                         */
   float *score_out;                 /* DEVICE fp32 [H, 3]                                           */
   int32_t H, d, Nq, Nc;
   int32_t q_sample_stride, q_offset; /* stride >= 1, 0 <= q_offset < min(stride, Nq)                */

@@ -37,6 +37,7 @@ class df_attn_args(C.Structure):
                 ("kc_stride_tok", C.c_int64), ("kc_stride_head", C.c_int64),
                 ("k_hist", C.c_void_p), ("v_hist", C.c_void_p),
                 ("hist_off", C.POINTER(C.c_int64)), ("hist_sink_len", C.POINTER(C.c_int32)),
+                ("hist_len", C.POINTER(C.c_int32)),
                 ("out", C.c_void_p), ("o_stride_tok", C.c_int64), ("o_stride_head", C.c_int64),
                 ("lse_out", C.c_void_p), ("score_out", C.c_void_p),
                 ("H", C.c_int32), ("d", C.c_int32), ("Nq", C.c_int32), ("Nc", C.c_int32),
@@ -49,6 +50,7 @@ class df_score_args(C.Structure):
                 ("k_cur", C.c_void_p), ("kc_stride_tok", C.c_int64), ("kc_stride_head", C.c_int64),
                 ("k_hist", C.c_void_p),
                 ("hist_off", C.POINTER(C.c_int64)), ("hist_sink_len", C.POINTER(C.c_int32)),
+                ("hist_len", C.POINTER(C.c_int32)),
                 ("score_out", C.c_void_p),
                 ("H", C.c_int32), ("d", C.c_int32), ("Nq", C.c_int32), ("Nc", C.c_int32),
                 ("q_sample_stride", C.c_int32), ("q_offset", C.c_int32),
@@ -151,9 +153,9 @@ def df_attn_workspace_bytes(H: int, d: int, Nq: int) -> int:
 
 
 def df_attn_fwd(q, k_cur, v_cur, k_hist, v_hist, hist_off, hist_sink_len, out, softmax_scale,
-                lse_out=None, score_out=None, workspace=None, stream=None):
+                lse_out=None, score_out=None, workspace=None, stream=None, hist_len=None):
     """q/out: [Nq, H, d] and k_cur/v_cur: [Nc, H, d] bf16 device tensors (any token/head strides,
-    d contiguous); k_hist/v_hist: [hist_off[-1], d] bf16; hist_off/hist_sink_len: python ints."""
+    d contiguous); k_hist/v_hist: [hist_off[-1], d] bf16; hist_off/hist_sink_len/hist_len: python ints."""
     a = df_attn_args()
     a.q, a.q_stride_tok, a.q_stride_head = _ptr(q), q.stride(0), q.stride(1)
     a.k_cur, a.v_cur = _ptr(k_cur), _ptr(v_cur)
@@ -164,6 +166,8 @@ def df_attn_fwd(q, k_cur, v_cur, k_hist, v_hist, hist_off, hist_sink_len, out, s
     a.hist_off = off
     sl = _i32(hist_sink_len) if hist_sink_len is not None else None
     a.hist_sink_len = sl
+    hl = _i32(hist_len) if hist_len is not None else None
+    a.hist_len = hl
     a.out, a.o_stride_tok, a.o_stride_head = _ptr(out), out.stride(0), out.stride(1)
     a.lse_out, a.score_out = _ptr(lse_out), _ptr(score_out)
     a.H, a.d, a.Nq, a.Nc = q.shape[1], q.shape[2], q.shape[0], k_cur.shape[0]
@@ -174,13 +178,15 @@ def df_attn_fwd(q, k_cur, v_cur, k_hist, v_hist, hist_off, hist_sink_len, out, s
 
 
 def df_head_score(q, k_cur, k_hist, hist_off, hist_sink_len, score_out, softmax_scale,
-                  q_sample_stride=4, q_offset=0, workspace=None, stream=None):
+                  q_sample_stride=4, q_offset=0, workspace=None, stream=None, hist_len=None):
     a = df_score_args()
     a.q, a.q_stride_tok, a.q_stride_head = _ptr(q), q.stride(0), q.stride(1)
     a.k_cur, a.kc_stride_tok, a.kc_stride_head = _ptr(k_cur), k_cur.stride(0), k_cur.stride(1)
     a.k_hist = _ptr(k_hist)
     off, sl = _i64(hist_off), _i32(hist_sink_len)
     a.hist_off, a.hist_sink_len = off, sl
+    hl = _i32(hist_len) if hist_len is not None else None
+    a.hist_len = hl
     a.score_out = _ptr(score_out)
     a.H, a.d, a.Nq, a.Nc = q.shape[1], q.shape[2], q.shape[0], k_cur.shape[0]
     a.q_sample_stride, a.q_offset = q_sample_stride, q_offset
@@ -217,6 +223,14 @@ class Cache:
         self.c.sink_len, self.c.win_len, self.c.win_pos = self.sink_len, self.win_len, self.win_pos
         self.c.H, self.c.d = H, d
         self.H, self.d = H, d
+
+    def in_place(self):
+        """(k_hist, v_hist, hist_off, hist_sink_len, hist_len) for reading the cache without packing:
+        the filled rows of a head are a prefix of its rows (sink rows, then the ring)."""
+        H = self.H
+        return (self.k_cache, self.v_cache, [int(self.head_row_off[h]) for h in range(H + 1)],
+                [int(self.sink_len[h]) for h in range(H)],
+                [int(self.sink_len[h]) + int(self.win_len[h]) for h in range(H)])
 
 
 def df_kv_append(cache: Cache, k_new, v_new, stream=None):

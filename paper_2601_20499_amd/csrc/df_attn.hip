@@ -101,6 +101,7 @@ struct AttnParams {
   float c;             // softmax_scale * log2(e)
   float scale;         // softmax_scale
   int64_t hist_off[kMaxHeads + 1];
+  int32_t hist_len[kMaxHeads];   // rows of each head that hold keys (a prefix of its rows)
   int32_t sink_len[kMaxHeads];
   uint8_t order[kMaxHeads];    // heads sorted by descending key count
 };
@@ -359,7 +360,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     while (pos >= p.cum[hh + 1]) ++hh;
     const int h = p.order[hh];
     const int64_t hoff = p.hist_off[h];
-    const int len_h = int(p.hist_off[h + 1] - hoff);
+    const int len_h = p.hist_len[h];
     const int sink = p.sink_len[h];
     const int nt0 = (sink + kKT - 1) / kKT;
     const int nt1 = (len_h - sink + kKT - 1) / kKT;
@@ -686,7 +687,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParam
   int n_tiles = 0;
   for (;; ++hh) {
     h = p.order[hh];
-    const int len_h = int(p.hist_off[h + 1] - p.hist_off[h]);
+    const int len_h = p.hist_len[h];
     const int sink = p.sink_len[h];
     n_tiles = (sink + kKT - 1) / kKT + (len_h - sink + kKT - 1) / kKT + (p.Nc + kKT - 1) / kKT;
     if (unit < p.n_qtiles) break;
@@ -786,7 +787,7 @@ static df_status launch(AttnParams &p, void *workspace, float *score_out, hipStr
   int64_t total = 0;
   for (int hh = 0; hh < p.H; ++hh) {
     const int h = p.order[hh];
-    const int64_t len = p.hist_off[h + 1] - p.hist_off[h];
+    const int64_t len = p.hist_len[h];
     const int64_t sink = p.sink_len[h];
     p.cum[hh] = int32_t(total);
     total += (sink + kKT - 1) / kKT + (len - sink + kKT - 1) / kKT + (p.Nc + kKT - 1) / kKT;
@@ -816,31 +817,34 @@ static df_status launch(AttnParams &p, void *workspace, float *score_out, hipStr
 
 // Checks shared by both entry points; fills the per-head tables of `p`.
 static df_status fill_heads(AttnParams &p, int H, int d, int Nq, int Nc, const int64_t *hist_off,
-                            const int32_t *sink_len, bool need_sink, const void *k_hist, const void *v_hist,
-                            bool need_v) {
+                            const int32_t *sink_len, const int32_t *hist_len, bool need_sink, const void *k_hist,
+                            const void *v_hist, bool need_v) {
   if (H <= 0 || Nq <= 0 || Nc <= 0) return DF_ERR_SHAPE;
   if (H > kMaxHeads || (d != 64 && d != 128)) return DF_ERR_UNSUPPORTED;
   if (!hist_off) return DF_ERR_NULL;
   if (need_sink && !sink_len) return DF_ERR_NULL;
   if (hist_off[0] != 0) return DF_ERR_RANGE;
+  int64_t any = 0;
   for (int h = 0; h < H; ++h) {
-    const int64_t len = hist_off[h + 1] - hist_off[h];
-    if (len < 0 || len * d * 2 >= kMaxBufferBytes) return DF_ERR_RANGE;
+    const int64_t rows = hist_off[h + 1] - hist_off[h];
+    if (rows < 0 || rows * d * 2 >= kMaxBufferBytes) return DF_ERR_RANGE;
+    const int64_t len = hist_len ? hist_len[h] : rows;
+    if (len < 0 || len > rows) return DF_ERR_RANGE;
     const int32_t sl = sink_len ? sink_len[h] : 0;
     if (sl < 0 || sl > len) return DF_ERR_RANGE;
     p.hist_off[h] = hist_off[h];
+    p.hist_len[h] = int32_t(len);
     p.sink_len[h] = sl;
+    any += len;
   }
   p.hist_off[H] = hist_off[H];
-  if (hist_off[H] > 0) {
+  if (any > 0) {
     if (!k_hist || (need_v && !v_hist)) return DF_ERR_NULL;
     if (!aligned16(k_hist) || (need_v && !aligned16(v_hist))) return DF_ERR_ALIGN;
   }
   int idx[kMaxHeads];
   std::iota(idx, idx + H, 0);
-  std::stable_sort(idx, idx + H, [&](int a, int b) {
-    return hist_off[a + 1] - hist_off[a] > hist_off[b + 1] - hist_off[b];
-  });
+  std::stable_sort(idx, idx + H, [&](int a, int b) { return p.hist_len[a] > p.hist_len[b]; });
   for (int h = 0; h < H; ++h) p.order[h] = uint8_t(idx[h]);
   p.H = H;
   p.Nq = Nq;
@@ -861,7 +865,7 @@ extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
   if (!a) return DF_ERR_NULL;
   if (!a->q || !a->k_cur || !a->v_cur || !a->out) return DF_ERR_NULL;
   AttnParams p{};
-  if (df_status s = fill_heads(p, a->H, a->d, a->Nq, a->Nc, a->hist_off, a->hist_sink_len,
+  if (df_status s = fill_heads(p, a->H, a->d, a->Nq, a->Nc, a->hist_off, a->hist_sink_len, a->hist_len,
                                a->score_out != nullptr, a->k_hist, a->v_hist, true))
     return s;
   if (!aligned16(a->q) || !aligned16(a->k_cur) || !aligned16(a->v_cur) || !aligned16(a->out))
@@ -897,7 +901,7 @@ extern "C" df_status df_head_score(const df_score_args *a, void *stream) {
   if (!a) return DF_ERR_NULL;
   if (!a->q || !a->k_cur || !a->score_out) return DF_ERR_NULL;
   AttnParams p{};
-  if (df_status s = fill_heads(p, a->H, a->d, a->Nq, a->Nc, a->hist_off, a->hist_sink_len, true,
+  if (df_status s = fill_heads(p, a->H, a->d, a->Nq, a->Nc, a->hist_off, a->hist_sink_len, a->hist_len, true,
                                a->k_hist, nullptr, false))
     return s;
   if (a->q_sample_stride < 1 || a->q_offset < 0 || a->q_offset >= a->q_sample_stride || a->q_offset >= a->Nq)

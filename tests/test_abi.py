@@ -151,6 +151,13 @@ def test_attn_argument_validation(b):
     assert b.lib.df_attn_fwd(C.byref(a), None) == E.DF_ERR_RANGE
     a, keep = _attn_args(b, hist_off=None)
     assert b.lib.df_attn_fwd(C.byref(a), None) == E.DF_ERR_NULL
+    for hl, code in [((10, 0, 21, 10), E.DF_ERR_RANGE),                      # more keys than the head has rows
+                     ((4, 0, 20, 10), E.DF_ERR_RANGE),                       # fewer keys than its sink region
+                     ((-1, 0, 20, 10), E.DF_ERR_RANGE)]:
+        a, keep = _attn_args(b)
+        keep["hl"] = (C.c_int32 * 4)(*hl)
+        a.hist_len = keep["hl"]
+        assert b.lib.df_attn_fwd(C.byref(a), None) == code, hl
     assert b.lib.df_attn_fwd(None, None) == E.DF_ERR_NULL
     assert b.df_attn_workspace_bytes(12, 128, 4680) >= 12 * 37 * 16 + 512 * 512 * 132
     assert b.df_attn_workspace_bytes(0, 128, 10) == 0

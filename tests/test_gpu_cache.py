@@ -100,3 +100,50 @@ def test_append_pack_attention_chain(df):
         for h in range(H):          # the oracle keeps the full chronological history; visibility does the rest
             hist_k[h] = np.concatenate([hist_k[h], kc[:, h].double().numpy()])
             hist_v[h] = np.concatenate([hist_v[h], vc[:, h].double().numpy()])
+
+
+def test_attention_reads_the_rolling_cache_in_place(df):
+    """Six autoregressive steps (the window ring wraps twice): attention straight on the cache
+    buffers (hist_len = filled rows per head, window keys in ring order) against the oracle, and
+    against attention on the packed, chronologically ordered context; also the fused scores, whose
+    sink / window split must not depend on the ring's rotation."""
+    H, d, T, C = 5, 128, 33, 3
+    types = [wl.HEAD_FULL, wl.HEAD_NEIGHBOR, wl.HEAD_DUMMY, wl.HEAD_PACK_DUMMY, wl.HEAD_SINK]
+    ctx = [df.df_head_context(t, T, 1, 4) for t in types]
+    sink_cap, win_cap = [c[0] for c in ctx], [c[1] for c in ctx]
+    cache = make_cache(df, H, d, sink_cap, win_cap, slack=5)
+    g = torch.Generator().manual_seed(10)
+    hist_k = [np.zeros((0, d)) for _ in range(H)]
+    hist_v = [np.zeros((0, d)) for _ in range(H)]
+    scale = 1 / np.sqrt(d)
+    cap_rows = sum(sink_cap) + sum(win_cap)
+    k_out = torch.zeros(cap_rows, d, dtype=torch.bfloat16, device=gu.dev())
+    v_out = torch.zeros(cap_rows, d, dtype=torch.bfloat16, device=gu.dev())
+    ws = torch.empty(df.df_attn_workspace_bytes(H, d, C * T), dtype=torch.uint8, device=gu.dev())
+    for step in range(6):
+        q = (torch.randn(C * T, H, d, generator=g) + 0.3).to(torch.bfloat16).to(gu.dev())
+        kc = torch.randn(C * T, H, d, generator=g).to(torch.bfloat16)
+        vc = torch.randn(C * T, H, d, generator=g).to(torch.bfloat16)
+        kcd, vcd = kc.to(gu.dev()), vc.to(gu.dev())
+        out_a = torch.empty(C * T, H, d, dtype=torch.bfloat16, device=gu.dev())
+        out_b = torch.empty_like(out_a)
+        F_a = torch.empty(H, 3, dtype=torch.float32, device=gu.dev())
+        F_b = torch.empty_like(F_a)
+        kh, vh, off, sl, hl = cache.in_place()
+        assert all(n <= off[h + 1] - off[h] for h, n in enumerate(hl))
+        df.df_attn_fwd(q, kcd, vcd, kh, vh, off, sl, out_a, scale, score_out=F_a, workspace=ws, hist_len=hl)
+        p_off, p_sl = df.df_pack_context(cache, sink_cap, win_cap, k_out, v_out)
+        assert [p_off[h + 1] - p_off[h] for h in range(H)] == hl and p_sl == sl
+        df.df_attn_fwd(q, kcd, vcd, k_out, v_out, p_off, p_sl, out_b, scale, score_out=F_b, workspace=ws)
+        df.df_kv_append(cache, kcd, vcd)
+        torch.cuda.synchronize()
+        ref, mass, _ = orc.layer_attention(q.cpu().double().numpy(), hist_k, hist_v, kc.double().numpy(),
+                                           vc.double().numpy(), sink_cap, win_cap, scale)
+        a, b = out_a.float().cpu().double().numpy(), out_b.float().cpu().double().numpy()
+        gu.check_out(a, ref, f"in place, step {step}")
+        assert np.abs(a - b).max() <= 2 ** -6, np.abs(a - b).max()      # same keys in another order: a bf16 ulp or two
+        np.testing.assert_allclose(F_a.cpu().numpy(), mass.mean(axis=1), atol=gu.F_ABS)
+        np.testing.assert_allclose(F_a.cpu().numpy(), F_b.cpu().numpy(), atol=2e-5)
+        for h in range(H):
+            hist_k[h] = np.concatenate([hist_k[h], kc[:, h].double().numpy()])
+            hist_v[h] = np.concatenate([hist_v[h], vc[:, h].double().numpy()])
