@@ -18,7 +18,7 @@ from . import binding as df
 H, D, CHUNK = 12, 128, 3
 
 
-def time_attn(T, frames_per_head, sink_frames_per_head, reps, dev):
+def time_attn(T, frames_per_head, sink_frames_per_head, reps, dev, H=H):
     """frames_per_head[h] = history frames head h sees; returns (ms, GFLOP)."""
     Nq = CHUNK * T
     lens = [f * T for f in frames_per_head]
@@ -101,6 +101,16 @@ def main():
             ("6 full + 6 packed dummy", [1] * 6 + [6] * 6, [0] * 6 + [1] * 6),
             ("6 packed dummy + 2 sink + 4 neighbour", [1] * 6 + [1] * 2 + [5] * 4, [0] * 6 + [1] * 2 + [0] * 4)]
     res = [(n, time_attn(8160, f, sk, max(3, a.reps // 4), dev)) for n, f, sk in rows]
+    for n, (ms, gf) in res:
+        print(f"| {n} | {gf:.0f} | {ms:.3f} | {gf / ms:.0f} | {res[0][1][0] / ms:.2f}x |", flush=True)
+
+    print()
+    print(f"### 40 heads per layer (14B-class geometry, T = {a.T}, 1 sink + 5 recent frames cached)")
+    print("| contexts of the 40 heads | GFLOP | ms | TFLOP/s | speedup |")
+    print("|---|---|---|---|---|")
+    rows = [("dense", [6] * 40, [1] * 40),
+            ("20 packed dummy + 7 sink + 13 neighbour", [1] * 20 + [1] * 7 + [5] * 13, [0] * 20 + [1] * 7 + [0] * 13)]
+    res = [(n, time_attn(a.T, f, sk, max(3, a.reps // 2), dev, H=40)) for n, f, sk in rows]
     for n, (ms, gf) in res:
         print(f"| {n} | {gf:.0f} | {ms:.3f} | {gf / ms:.0f} | {res[0][1][0] / ms:.2f}x |", flush=True)
 

@@ -43,3 +43,16 @@ def test_1080p_chunk(df):
     w = wl.res1080p()
     assert w.Nq == 24480 and w.Nq % 256 != 0
     check(df, w, 24, seed=8)
+
+
+def test_forty_heads_per_layer(df):
+    """A layer of the 14B-class geometry (40 heads of width 128; the paper gives only the 1600-head
+    total): every head type in one call, more heads than any other test, element-wise parity."""
+    types = ([wl.HEAD_PACK_DUMMY] * 20 + [wl.HEAD_SINK] * 6 + [wl.HEAD_NEIGHBOR] * 10 + [wl.HEAD_FULL] * 3
+             + [wl.HEAD_DUMMY])
+    w = wl.small_ragged(77, H=40, d=128, T=90, hist_frames=6, types=types, planted=list(range(20)))
+    out, score, lse = gu.run_attn(df, w)
+    ref, mass, ref_lse = gu.oracle_rows(w)
+    gu.check_out(out, ref, w.name)
+    assert np.abs(lse - ref_lse).max() <= gu.LSE_ABS
+    np.testing.assert_allclose(score, mass.mean(axis=1), atol=gu.F_ABS)
