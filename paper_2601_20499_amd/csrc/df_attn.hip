@@ -46,7 +46,7 @@
 // reads per ds_read_b128 fall into distinct banks, with 64 B per V group the
 // four consecutive keys of a ds_read_b64_tr_b16 do, and every operand address
 // is still "lane base + compile-time offset".  Tiles rotate through four LDS
-// buffers each; loads are issued three phases before their first use.
+// buffers each; loads are issued two to three iterations before their first use.
 //
 // Online softmax keeps a running row maximum m and per-lane partial row sums
 // l in fp32.  The maximum is only raised (and O, l rescaled) when some row of
