@@ -47,8 +47,9 @@ __global__ __launch_bounds__(kCopyThreads) void df_rows_kernel(const CopyParams 
   const HeadPlan &pl = p.plan[blockIdx.y];
   constexpr int rv = RV;
   const int n_vec = (pl.n_a + pl.n_b) * rv;
-  const int v0 = blockIdx.x * kVecPerBlock + threadIdx.x;
-  if (blockIdx.x * kVecPerBlock >= n_vec) return;
+  const int block_v0 = int(blockIdx.x) * kVecPerBlock;
+  if (block_v0 >= n_vec) return;
+  const int v0 = block_v0 + int(threadIdx.x);
   const vec16 *__restrict__ src = blockIdx.z ? p.src_v : p.src_k;
   vec16 *__restrict__ dst = blockIdx.z ? p.dst_v : p.dst_k;
   constexpr int kPer = kVecPerBlock / kCopyThreads;
