@@ -137,3 +137,65 @@ def test_config5_long_context_sampled_rows(df):
     lens = sorted(w.visible_len(h) for h in range(w.H))
     assert lens[0] == 0 and lens[6] == 4680 and lens[-1] == 93600
     _sampled_parity(df, w, 64, seed=5)
+
+
+def _direct(df, q, kc, vc, kh, vh, off, sl, scale, want_score=True):
+    """df_attn_fwd on explicit tensors (queries and current keys may differ in number)."""
+    d = gu.dev()
+    H, dd = q.shape[1], q.shape[2]
+    out = torch.full(q.shape, float("nan"), dtype=torch.bfloat16, device=d)
+    score = torch.full((H, 3), float("nan"), dtype=torch.float32, device=d) if want_score else None
+    ws = torch.empty(df.df_attn_workspace_bytes(H, dd, q.shape[0]), dtype=torch.uint8, device=d)
+    df.df_attn_fwd(q.to(d), kc.to(d), vc.to(d), kh.to(d), vh.to(d), off, sl, out, scale, score_out=score, workspace=ws)
+    torch.cuda.synchronize()
+    return out.float().cpu().double().numpy(), (None if score is None else score.cpu().double().numpy())
+
+
+def _oracle_direct(q, kc, vc, kh_list, vh_list, n_sink, n_win, scale, rows=None):
+    from oracle import df_oracle as orc
+    b = lambda t: t.double().numpy()
+    return orc.layer_attention(b(q), [b(x) for x in kh_list], [b(x) for x in vh_list], b(kc), b(vc),
+                               n_sink, n_win, scale, rows=rows)
+
+
+def test_more_query_tiles_than_compute_units(df):
+    """65 797 queries = 258 query tiles > 256 CUs: a team then passes over the query tiles in rounds.
+    Few keys (30 of history, 40 current), so the oracle covers every row."""
+    g = torch.Generator().manual_seed(21)
+    Nq, Nc, Nh, H, d = 256 * 257 + 5, 40, 30, 2, 64
+    mk = lambda *s: torch.randn(*s, generator=g).to(torch.bfloat16)
+    q, kc, vc = mk(Nq, H, d), mk(Nc, H, d), mk(Nc, H, d)
+    kh, vh = mk(Nh, H, d), mk(Nh, H, d)
+    # head 0 sees 10 sink + 20 window keys, head 1 nothing but the current keys
+    k_p, v_p = kh[:, 0].contiguous(), vh[:, 0].contiguous()
+    out, score = _direct(df, q, kc, vc, k_p, v_p, [0, Nh, Nh], [10, 0], d ** -0.5)
+    ref, mass, _ = _oracle_direct(q, kc, vc, [kh[:, 0], kh[:, 1]], [vh[:, 0], vh[:, 1]], [10, 0], [20, 0], d ** -0.5)
+    gu.check_out(out, ref, "258 query tiles")
+    np.testing.assert_allclose(score, mass.mean(axis=1), atol=gu.F_ABS)
+
+
+def test_sixty_four_heads_and_a_single_query(df):
+    """The most heads a call takes (DF_MAX_HEADS) and the fewest queries and current keys (one each)."""
+    g = torch.Generator().manual_seed(22)
+    H, d, Nh = 64, 128, 70
+    mk = lambda *s: torch.randn(*s, generator=g).to(torch.bfloat16)
+    q, kc, vc = mk(1, H, d), mk(1, H, d), mk(1, H, d)
+    kh, vh = mk(Nh, H, d), mk(Nh, H, d)
+    lens = [(h * 7) % (Nh + 1) for h in range(H)]            # 0 .. 70 keys of history, odd lengths
+    sinks = [min(n, h % 5) for h, n in enumerate(lens)]
+    off = [0]
+    for n in lens:
+        off.append(off[-1] + n)
+    # head h keeps its first sinks[h] rows and its last lens[h]-sinks[h] rows
+    rows = [torch.cat([torch.arange(0, s), torch.arange(Nh - (n - s), Nh)]) for n, s in zip(lens, sinks)]
+    k_p = torch.cat([kh[r, h] for h, r in enumerate(rows)])
+    v_p = torch.cat([vh[r, h] for h, r in enumerate(rows)])
+    out, score = _direct(df, q, kc, vc, k_p, v_p, off, sinks, d ** -0.5)
+    ref, mass, _ = _oracle_direct(q, kc, vc, [kh[:, h] for h in range(H)], [vh[:, h] for h in range(H)],
+                                  sinks, [n - s for n, s in zip(lens, sinks)], d ** -0.5)
+    gu.check_out(out, ref, "64 heads, one query")
+    np.testing.assert_allclose(score, mass.mean(axis=1), atol=gu.F_ABS)
+    with pytest.raises(df.DfError) as e:                       # one head more is refused, nothing launched
+        q65 = mk(1, 65, d)
+        _direct(df, q65, q65, q65, k_p, v_p, off + [off[-1]], sinks + [0], d ** -0.5)
+    assert e.value.status == df.DF_ERR_UNSUPPORTED
