@@ -408,43 +408,47 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     };
 
     // Inside the tile loop the loads follow two cursors (K three tiles ahead, V two), advanced by one
-    // tile per iteration: byte offset += keys per tile * row stride, except at the few tiles where a
-    // cursor enters the window region, the current chunk or the end of the piece.  That keeps the
-    // scalar work per iteration to a handful of instructions.
-    struct Cursor { int t; uint32_t toff; uint32_t step; int next_event; bool cur; };
-    auto locate = [&](int t) {
-      Cursor c;
-      c.t = t;
-      c.cur = false;
-      if (t >= t_end) { c.toff = kNoTile; c.step = 0; c.next_event = INT32_MAX; }
-      else if (t < nt0) { c.toff = uint32_t(t * kKT) * L::ROWB; c.step = kKT * L::ROWB; c.next_event = min(nt0, t_end); }
-      else if (t < nt0 + nt1) {
-        c.toff = uint32_t(sink + (t - nt0) * kKT) * L::ROWB; c.step = kKT * L::ROWB; c.next_event = min(nt0 + nt1, t_end);
+    // tile per iteration: byte offset += keys per tile * row stride, LDS buffer rotated, and only at
+    // the few tiles where a cursor enters the window region, the current chunk or the end of the piece
+    // are offset, step and descriptor worked out again.  That keeps the scalar work per iteration
+    // to a handful of instructions.
+    struct Cursor {
+      int t, next_event;            // tile under the cursor; first tile at which step/descriptor change
+      uint32_t vo;                  // per lane: byte offset of this lane's 16 bytes of the wave's first row group
+      uint32_t step, step_g;        // bytes per tile; bytes between the wave's row groups (kWaves rows apart)
+      bool cur;                     // read through the current-chunk descriptor (else the history's)
+      unsigned dst;                 // LDS byte address of the wave's first row group in the tile's buffer
+    };
+    auto relocate = [&](Cursor &c) {
+      const int t = c.t;
+      if (t >= t_end) {             // absent tile: out of range for every lane, the loads write zeros
+        c.vo = kNoTile; c.step = 0; c.step_g = 0; c.next_event = INT32_MAX;
+        c.cur = true;
+      } else if (t < nt0 + nt1) {
+        const uint32_t row0 = t < nt0 ? uint32_t(t * kKT) : uint32_t(sink + (t - nt0) * kKT);
+        c.vo = lane_vo_hist + row0 * L::ROWB; c.step = kKT * L::ROWB; c.step_g = kWaves * L::ROWB;
+        c.next_event = min(t < nt0 ? nt0 : nt0 + nt1, t_end);
+        c.cur = false;
       } else {
-        c.cur = true; c.toff = uint32_t((t - nt0 - nt1) * kKT) * cur_stride_b; c.step = kKT * cur_stride_b; c.next_event = t_end;
+        c.vo = lane_vo_cur + uint32_t((t - nt0 - nt1) * kKT) * cur_stride_b;
+        c.step = kKT * cur_stride_b; c.step_g = kWaves * cur_stride_b; c.next_event = t_end;
+        c.cur = true;
       }
-      return c;
     };
-    auto advance = [&](Cursor &c) {
+    // one tile on: next LDS buffer, next tile's bytes; then this wave's share of that tile goes out
+    auto advance_and_load = [&](Cursor &c, bool is_v) {
+      const unsigned tile_b = is_v ? L::VTILE : L::KTILE, gs = is_v ? L::VGS : L::KGS;
+      const unsigned base = (is_v ? lds_address(lds_v) : lds_address(lds_k)) + wave * gs;
       ++c.t;
-      c.toff += c.step;
-      if (c.t == c.next_event) c = locate(c.t);
-    };
-    // this wave's share of the tile under cursor c into the LDS tile at byte address dst
-    auto dma_cursor = [&](const Cursor &c, unsigned dst, bool is_v) {
-      const int gs = is_v ? L::VGS : L::KGS;
-      if (c.cur) {
-        const uint32_t vo = lane_vo_cur + c.toff;
+      c.vo += c.step;
+      c.dst = (c.dst == base + (kNBuf - 1) * tile_b) ? base : c.dst + tile_b;
+      if (c.t == c.next_event) relocate(c);
 #pragma unroll
-        for (int i = 0; i < GPW; ++i)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vc : rs_kc, (lds_void *)(uintptr_t)(dst + (wave + kWaves * i) * gs),
-                                                   16, int(vo + uint32_t(kWaves * i) * cur_stride_b), 0, 0, 0);
-      } else {
-        const uint32_t vo = lane_vo_hist + c.toff;
-#pragma unroll
-        for (int i = 0; i < GPW; ++i)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vh : rs_kh, (lds_void *)(uintptr_t)(dst + (wave + kWaves * i) * gs),
-                                                   16, int(vo + uint32_t(kWaves * i) * L::ROWB), 0, 0, 0);
+      for (int i = 0; i < GPW; ++i) {
+        lds_void *d = (lds_void *)(uintptr_t)(c.dst + kWaves * i * gs);
+        const int vo = int(c.vo + uint32_t(i) * c.step_g);
+        if (c.cur) __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vc : rs_kc, d, 16, vo, 0, 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vh : rs_kh, d, 16, vo, 0, 0, 0);
       }
     };
 
@@ -492,19 +496,19 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) pb[kb][ts][e] = (__bf16)0.f;
     int k_slot = 0, v_slot = kNBuf - 1;      // LDS buffer of K(t) and of V(t-1)
-    Cursor kc = locate(t_begin + 2), vc = locate(t_begin + 1);   // the last tiles the prologue has issued
-    unsigned kd_slot = 2, vd_slot = 1;                           // and their LDS buffers
+    // the cursors start on the last tiles the prologue has issued (K: t_begin + 2 in buffer 2, V: t_begin + 1 in buffer 1)
+    Cursor kc, vc;
+    kc.t = t_begin + 2;
+    kc.dst = lds_address(lds_k) + wave * L::KGS + 2 * L::KTILE;
+    relocate(kc);
+    vc.t = t_begin + 1;
+    vc.dst = lds_address(lds_v) + wave * L::VGS + 1 * L::VTILE;
+    relocate(vc);
     // every wave issues the same number of loads once per VALU phase (absent tiles load zeros), so
     // the s_waitcnt count at the end of the MFMA phase holds
     auto phase_loads = [&]() {
-      advance(kc);
-      kd_slot = (kd_slot + 1) % kNBuf;
-      dma_cursor(kc, lds_address(lds_k) + kd_slot * L::KTILE, false);
-      if (!SCORE_ONLY) {
-        advance(vc);
-        vd_slot = (vd_slot + 1) % kNBuf;
-        dma_cursor(vc, lds_address(lds_v) + vd_slot * L::VTILE, true);
-      }
+      advance_and_load(kc, false);
+      if (!SCORE_ONLY) advance_and_load(vc, true);
     };
 
     const int seg_end0 = nt0 - 1, seg_end1 = nt0 + nt1 - 1;
