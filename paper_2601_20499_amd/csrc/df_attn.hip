@@ -512,13 +512,19 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     };
 
     const int seg_end0 = nt0 - 1, seg_end1 = nt0 + nt1 - 1;
+    // last tile of the segment that tile t lies in (empty segments have no tiles)
+    auto seg_end_from = [&](int t) { return t < nt0 ? seg_end0 : (t < nt0 + nt1 ? seg_end1 : n_tiles - 1); };
+    int next_seg_end = seg_end_from(t_begin);
     float mx = 0.f, mx4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
     for (int t = t_begin; t <= t_end; ++t) {
-      int n_valid_t = kKT;                    // real keys in tile t
-      if (t == seg_end0) n_valid_t = sink - (nt0 - 1) * kKT;
-      else if (t == seg_end1) n_valid_t = len_h - sink - (nt1 - 1) * kKT;
-      else if (t == n_tiles - 1) n_valid_t = p.Nc - (nt2 - 1) * kKT;
+      int n_valid_t = kKT;                    // real keys in tile t: only a segment's last tile can be partial
+      if (t == next_seg_end) {
+        if (t == seg_end0) n_valid_t = sink - (nt0 - 1) * kKT;
+        else if (t == seg_end1) n_valid_t = len_h - sink - (nt1 - 1) * kKT;
+        else n_valid_t = p.Nc - (nt2 - 1) * kKT;
+        next_seg_end = seg_end_from(t + 1);
+      }
       // ================= MFMA phase =================
       // Always both products: at the first tile the second one multiplies P = 0 with the zero-filled
       // spare V buffer, after the last tile the first one computes scores of a stale tile that nobody reads.
