@@ -287,3 +287,72 @@ def test_planted_heads_put_most_mass_on_the_current_chunk():
             assert F[2] > 0.8
         else:
             np.testing.assert_allclose(F, [1 / 9, 5 / 9, 3 / 9], atol=0.06)
+
+
+# ------------------------------------------- layer_attention: head slicing, pinned head by head
+def _brute_lse(q, kh, kc, n_sink, n_win, scale):
+    """log sum_v exp(scale q.k_v) over the visible keys, python floats, from the definition."""
+    Nh = len(kh)
+    keys = [kh[j] for j in range(Nh) if j < n_sink or j >= Nh - n_win] + list(kc)
+    out = []
+    for qu in q:
+        logits = [scale * sum(a * b for a, b in zip(qu, kr)) for kr in keys]
+        mx = max(logits)
+        out.append(mx + math.log(sum(math.exp(s - mx) for s in logits)))
+    return np.array(out)
+
+
+def _distinct_heads_case():
+    """Four heads that differ in everything layer_attention has to route per head: Q, K, V of the
+    current chunk, history length and content, n_sink, n_win; head 2 has no history at all."""
+    rng = np.random.default_rng(77)
+    Nq, Nc, H, d = 5, 4, 4, 3
+    q, kc, vc = _rand(rng, Nq, H, d), _rand(rng, Nc, H, d), _rand(rng, Nc, H, d)
+    q *= np.array([0.5, 1.0, 2.0, 3.0])[None, :, None]          # heads differ in scale as well
+    Nh = [7, 5, 0, 9]
+    kh = [_rand(rng, n, d) for n in Nh]
+    vh = [_rand(rng, n, d) + 3.0 * h for h, n in enumerate(Nh)]  # a per-head offset: a V mix-up cannot hide
+    vc = vc + np.array([10.0, -10.0, 20.0, -20.0])[None, :, None]
+    n_sink, n_win = [2, 0, 3, 4], [3, 4, 2, 0]
+    return q, kh, vh, kc, vc, n_sink, n_win, 0.6
+
+
+def _check_layer_against_brute(layer_fn):
+    q, kh, vh, kc, vc, n_sink, n_win, scale = _distinct_heads_case()
+    H = q.shape[1]
+    for rows in (None, np.array([4, 0, 2])):
+        out, mass, lse = layer_fn(q, kh, vh, kc, vc, n_sink, n_win, scale, rows=rows)
+        sel = np.arange(q.shape[0]) if rows is None else rows
+        assert out.shape == (len(sel), H, q.shape[2]) and mass.shape == (H, len(sel), 3) and lse.shape == (H, len(sel))
+        for h in range(H):
+            bo, bm = _brute_head(q[sel, h].tolist(), kh[h].tolist(), vh[h].tolist(), kc[:, h].tolist(),
+                                 vc[:, h].tolist(), n_sink[h], n_win[h], scale)
+            bl = _brute_lse(q[sel, h].tolist(), kh[h].tolist(), kc[:, h].tolist(), n_sink[h], n_win[h], scale)
+            np.testing.assert_allclose(out[:, h], bo, rtol=1e-12, atol=1e-12, err_msg=f"out, head {h}")
+            np.testing.assert_allclose(mass[h], bm, rtol=1e-12, atol=1e-13, err_msg=f"mass, head {h}")
+            np.testing.assert_allclose(lse[h], bl, rtol=1e-12, atol=1e-12, err_msg=f"lse, head {h}")
+
+
+def test_layer_attention_distinct_heads_against_brute_force():
+    """layer_attention is what every GPU parity test calls: out, region masses and LSE of every
+    head against the python-float brute force run head by head, with and without a row subset."""
+    _check_layer_against_brute(orc.layer_attention)
+
+
+@pytest.mark.parametrize("old,new", [
+    ("np.asarray(v_cur)[:, h, :]", "np.asarray(v_cur)[:, 0, :]"),          # wrong head of V_cur
+    ("np.asarray(k_cur)[:, h, :]", "np.asarray(k_cur)[:, (h + 1) % H, :]"),  # wrong head of K_cur
+    ("v_hist_list[h]", "v_hist_list[min(h, 1)]"),                          # wrong head's cached values
+    ("q[rows, h, :]", "q[rows, H - 1 - h, :]"),                            # wrong head of Q
+    ("n_sink[h], n_win[h]", "n_win[h], n_sink[h]"),                        # sink / window swapped
+])
+def test_the_layer_pin_catches_planted_head_index_mistakes(old, new):
+    """The pin above must fail on a scratch copy of the oracle with one routing mistake planted."""
+    import inspect
+    import types
+    src = inspect.getsource(orc)
+    assert src.count(old) == 1, old
+    mutant = types.ModuleType("df_oracle_mutant")
+    exec(compile(src.replace(old, new), "df_oracle_mutant", "exec"), mutant.__dict__)
+    with pytest.raises((AssertionError, ValueError, IndexError)):
+        _check_layer_against_brute(mutant.layer_attention)

@@ -29,10 +29,19 @@ def test_cache_ratio_accounting_matches_printed_table():
 
 
 def test_context_ratio_matches_printed_table():
+    """Tab. 5's context ratio is the cached frames of a neighbour head over the 36-frame sliding
+    window: the oracle's per-type context (Eq. 5) and its frame accounting must print the same."""
     rows = {r[0]: (int(r[1]), float(r[2])) for r in _table("tab5_context_ratio.txt")}
+    T = 1560
     base = rows["longlive_window"][0]
     for name, (frames, ratio) in rows.items():
-        assert round(frames / base, 2) == ratio
+        # every head of the two baselines, and the neighbour heads of the method, see `frames` past frames
+        n_sink, n_win = orc.head_context_tokens(orc.HEAD_NEIGHBOR, T, 1, frames)
+        assert (n_sink, n_win) == (0, frames * T)
+        assert round(orc.cache_kept_fraction([n_win / T], base), 2) == ratio, name
+    # the method's other heads keep one frame each (sink or packing frame): far below the window
+    for t in (orc.HEAD_SINK, orc.HEAD_PACK_DUMMY):
+        assert sum(orc.head_context_tokens(t, T, 1, rows["dummy_forcing"][0])) == T
 
 
 def test_head_context_tokens_per_type():
