@@ -70,16 +70,16 @@ def test_full_size_layer_with_three_head_types(df, layer):
     apply_types(df, w, types)
     assert {df.DF_HEAD_PACK_DUMMY} <= set(w.head_type) and len(set(w.head_type)) >= 2
     out, score, lse = gu.run_attn(df, w)
-    rows = gu.sample_rows(w.Nq, 40, seed=100 + layer)
-    ref, mass, ref_lse = gu.oracle_rows(w, rows=rows)
-    gu.check_out(out[rows], ref, w.name)
-    assert np.abs(lse[:, rows] - ref_lse).max() <= gu.LSE_ABS
+    ref, mass, ref_lse = gu.oracle_rows(w)                      # every row: the fused score is a mean over all of them
+    gu.check_out(out, ref, w.name)
+    assert np.abs(lse - ref_lse).max() <= gu.LSE_ABS
     # fused scores are under each head's own visibility: a sink head has no neighbour mass and
-    # the other way round; the sampled rows' mean masses bound the full means loosely
+    # the other way round
     for h, t in enumerate(w.head_type):
         if t == df.DF_HEAD_SINK:
             assert score[h, 1] == 0.0
         if t in (df.DF_HEAD_NEIGHBOR, df.DF_HEAD_PACK_DUMMY):
             assert score[h, 0] == 0.0
     np.testing.assert_allclose(score.sum(1), 1.0, atol=1e-5)
-    np.testing.assert_allclose(score, mass.mean(axis=1), atol=0.05)
+    print(f"layer {layer}: fused F max err {np.abs(score - mass.mean(axis=1)).max():.2e}", flush=True)
+    np.testing.assert_allclose(score, mass.mean(axis=1), atol=gu.F_ABS)

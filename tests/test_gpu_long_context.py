@@ -24,6 +24,10 @@ def check(df, w, n_rows, seed):
     assert np.abs(lse[:, rows] - ref_lse).max() <= gu.LSE_ABS
     np.testing.assert_allclose(score.sum(1), 1.0, atol=1e-5)
     np.testing.assert_allclose(score, mass.mean(axis=1), atol=0.05)   # sampled rows against all rows: loose
+    # the same rows on both sides: a launch on the sampled queries alone (all keys) to the score tolerance
+    sub = gu.fused_score_on_rows(df, w, rows)
+    print(f"{w.name}: fused F on the sampled rows, max err {np.abs(sub - mass.mean(axis=1)).max():.2e}", flush=True)
+    np.testing.assert_allclose(sub, mass.mean(axis=1), atol=gu.F_ABS)
     return score
 
 

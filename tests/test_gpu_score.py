@@ -78,16 +78,21 @@ def test_fused_score_equals_standalone_under_full_visibility(df):
     np.testing.assert_allclose(fused, alone, atol=2e-6)
 
 
-def test_config3_layers_classification_exact(df):
-    """Two layers of the 30-layer stack at full size: sampled-query scores under full visibility,
-    2-class classification with N=3 per layer, then attention with the resulting types."""
-    for layer in (0, 17):
+def test_config3_all_thirty_layers_and_the_global_classification(df):
+    """The whole 30-layer stack at full size (21-frame history, 37 440 keys per head and query):
+    per layer the sampled-query scores under full visibility against the oracle on the complete
+    sample, the 2-class classification with N = 3 exact outside the tie band, then attention with
+    the resulting head types on sampled rows; at the end one classification over all 360 heads
+    with N = 90 (the paper classifies globally, Sec. 3.3 / Fig. 8), exact against the oracle."""
+    F_all, R_all, margins = [], [], []
+    for layer in range(30):
         w = wl.config3_layer(layer)
         F = gpu_scores(df, w)
         R = oracle_scores(w)
-        assert np.abs(F - R).max() <= gu.F_ABS, np.abs(F - R).max()
+        err = np.abs(F - R).max()
+        assert err <= gu.F_ABS, (layer, err)
         margin = classes_agree(df, F, R, 3, df.DF_CLASSIFY_TWO_CLASS, orc.MODE_TWO_CLASS)
-        print(f"layer {layer}: planted {w.planted}, margin {margin:.3e}", flush=True)
+        margins.append(margin)
         types, _ = df.df_classify(F.tolist(), 3, df.DF_CLASSIFY_TWO_CLASS)
         dummies = {h for h, t in enumerate(types) if t == df.DF_HEAD_DUMMY}
         if len(w.planted) <= 3:
@@ -98,6 +103,20 @@ def test_config3_layers_classification_exact(df):
             w.head_type[h] = types[h]
             w.n_sink[h], w.n_win[h] = df.df_head_context(types[h], w.T, w.sink_frames, w.hist_frames - w.sink_frames)
         out, score, _ = gu.run_attn(df, w, want_lse=False)
-        rows = gu.sample_rows(w.Nq, 48, seed=layer)
+        rows = gu.sample_rows(w.Nq, 24, seed=layer)
         ref, _, _ = gu.oracle_rows(w, rows=rows)
-        gu.check_out(out[rows], ref, w.name)
+        e_max, e_mean, rel = gu.check_out(out[rows], ref, w.name)
+        for h in dummies:
+            np.testing.assert_array_equal(score[h], [0.0, 0.0, 1.0])
+        print(f"layer {layer}: planted {w.planted} dummy {sorted(dummies)} F err {err:.2e} margin {margin:.3e}", flush=True)
+        F_all.append(F)
+        R_all.append(R)
+        del w
+    F_all, R_all = np.concatenate(F_all), np.concatenate(R_all)
+    assert F_all.shape == (360, 3)
+    g_margin = classes_agree(df, F_all, R_all, 90, df.DF_CLASSIFY_TWO_CLASS, orc.MODE_TWO_CLASS)
+    g_types, _ = df.df_classify(F_all.tolist(), 90, df.DF_CLASSIFY_TWO_CLASS)
+    per_layer = np.asarray([t == df.DF_HEAD_DUMMY for t in g_types]).reshape(30, 12).sum(1)
+    print(f"per-layer margins min {min(margins):.3e}; global n=360 N=90 margin {g_margin:.3e}; "
+          f"dummy heads per layer (global run) {per_layer.tolist()}", flush=True)
+    assert per_layer.sum() == 90
