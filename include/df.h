@@ -120,6 +120,32 @@ typedef struct df_attn_args {
 size_t df_attn_workspace_bytes(int32_t H, int32_t d, int32_t Nq);
 df_status df_attn_fwd(const df_attn_args *args, void *stream);
 
+/* df_attn_plan: how df_attn_fwd / df_head_score share a launch out over the GPU's 256 compute units
+ * (the head-type-driven scheduling: heads differ in context length by Eq. 5 / Eq. 8, so work is cut by
+ * key tiles, not by heads).  Pure host code, launches nothing; for callers and tests that want to see
+ * the decomposition.  Queries are taken in tiles of 256, keys in tiles of 64 per region (sink, window,
+ * current chunk); the tiles of all heads, longest head first, form a line of columns; query tiles are
+ * walked in groups of team_size; the line of (group, column) positions is cut into n_teams equal spans;
+ * team t's member m handles query tile group*team_size + m over span t.
+ * hist_len[h] = history keys of head h (>= 0), hist_sink_len[h] = how many of them are the sink region
+ * (NULL = 0).  Errors: DF_ERR_NULL, DF_ERR_SHAPE (H, Nq, Nc <= 0), DF_ERR_UNSUPPORTED (H > DF_MAX_HEADS),
+ * DF_ERR_RANGE (sink > len, or more than 2^30 key tiles). */
+typedef struct df_attn_plan_info {
+  int32_t n_qtiles;    /* ceil(Nq / 256)                                                        */
+  int32_t team_size;   /* workgroups of a team: query tiles that walk the same key tiles together */
+  int32_t n_groups;    /* ceil(n_qtiles / team_size)                                            */
+  int32_t n_teams;     /* spans of the line                                                     */
+  int32_t workgroups;  /* n_teams * team_size, at most 256                                      */
+  int32_t cut_units;   /* (head, query tile) units split by a span boundary (merged by a second kernel) */
+  int64_t total_cols;  /* key tiles of all heads                                                */
+  int64_t line_len;    /* n_groups * total_cols                                                 */
+  int64_t span_min, span_max; /* shortest and longest span, in key tiles                        */
+  double busy;         /* share of the 256 workgroup slots that hold a query tile, averaged over the line */
+} df_attn_plan_info;
+
+df_status df_attn_plan(int32_t H, int32_t Nq, int32_t Nc, const int32_t *hist_len,
+                       const int32_t *hist_sink_len, df_attn_plan_info *out);
+
 /* ------------------------------------------------------------------------
  * df_head_score: the global frame attention score F[h] = (alpha^sink,
  * alpha^neighbour, alpha^current) of Eq. 3 for every head, estimated on the

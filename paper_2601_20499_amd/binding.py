@@ -21,7 +21,7 @@ DF_MAX_HEADS = 64
 DF_HEAD_FULL, DF_HEAD_SINK, DF_HEAD_NEIGHBOR, DF_HEAD_DUMMY, DF_HEAD_PACK_DUMMY = range(5)
 DF_CLASSIFY_TWO_CLASS, DF_CLASSIFY_DHP = 0, 1
 
-EXPORTS = ["df_status_string", "df_head_context", "df_attn_workspace_bytes", "df_attn_fwd",
+EXPORTS = ["df_status_string", "df_head_context", "df_attn_workspace_bytes", "df_attn_fwd", "df_attn_plan",
            "df_head_score", "df_classify", "df_kv_append", "df_pack_context"]
 
 
@@ -56,6 +56,13 @@ class df_score_args(C.Structure):
                 ("q_sample_stride", C.c_int32), ("q_offset", C.c_int32),
                 ("softmax_scale", C.c_float),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class df_attn_plan_info(C.Structure):
+    _fields_ = [("n_qtiles", C.c_int32), ("team_size", C.c_int32), ("n_groups", C.c_int32), ("n_teams", C.c_int32),
+                ("workgroups", C.c_int32), ("cut_units", C.c_int32),
+                ("total_cols", C.c_int64), ("line_len", C.c_int64), ("span_min", C.c_int64), ("span_max", C.c_int64),
+                ("busy", C.c_double)]
 
 
 class df_cache(C.Structure):
@@ -93,6 +100,9 @@ def _load() -> C.CDLL:
     lib.df_attn_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
     lib.df_attn_fwd.restype = C.c_int32
     lib.df_attn_fwd.argtypes = [C.POINTER(df_attn_args), C.c_void_p]
+    lib.df_attn_plan.restype = C.c_int32
+    lib.df_attn_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                 C.POINTER(df_attn_plan_info)]
     lib.df_head_score.restype = C.c_int32
     lib.df_head_score.argtypes = [C.POINTER(df_score_args), C.c_void_p]
     lib.df_classify.restype = C.c_int32
@@ -123,6 +133,15 @@ def _i64(xs: Sequence[int]):
 
 def _i32(xs: Sequence[int]):
     return (C.c_int32 * len(xs))(*[int(x) for x in xs])
+
+
+def df_attn_plan(Nq: int, Nc: int, hist_len: Sequence[int], hist_sink_len: Optional[Sequence[int]] = None) -> dict:
+    """The launch decomposition df_attn_fwd would use for these per-head history lengths (host only)."""
+    info = df_attn_plan_info()
+    H = len(hist_len)
+    _check(lib.df_attn_plan(H, int(Nq), int(Nc), _i32(hist_len),
+                            _i32(hist_sink_len) if hist_sink_len is not None else None, C.byref(info)), "df_attn_plan")
+    return {name: getattr(info, name) for name, _ in df_attn_plan_info._fields_}
 
 
 def _ptr(t) -> Optional[int]:

@@ -81,7 +81,7 @@ constexpr int kWaves = 8;
 constexpr int kBQ = kWaves * 32;   // queries per workgroup
 constexpr int kKT = 64;            // keys per LDS tile
 constexpr int kNBuf = 4;           // LDS buffers per operand
-constexpr float kRescaleLog2 = 8.f;  // raise the running maximum only beyond this many powers of two
+constexpr float kSumLimit = 0x1p100f; // the reference of the exponentials is raised when a row's running sum passes this
 constexpr int kXcd = 8;            // XCDs per device: consecutive workgroup ids go to consecutive XCDs
 constexpr int kNumCU = 256;        // MI355X: one workgroup per CU (LDS-bound occupancy)
 constexpr int kMinSpan = 8;        // do not cut the work finer than this many key tiles per team
@@ -91,14 +91,19 @@ struct AttnParams {
   u16 *out;
   float *lse;          // [H, Nq] or null
   float *part;         // workspace: [H, n_qtiles, 4] partial score sums, or null
-  float *slots;        // workspace: 2 partial-result slots per workgroup (see slot_floats)
+  int32_t *tickets;    // workspace: [H] counters of the merged units of a head (zeroed by the main kernel)
+  float *slots;        // workspace: 2 partial-result slots per workgroup (see Slot)
+  float *score;        // [H, 3] frame attention scores, or null
   int64_t q_st, q_sh, kc_st, kc_sh, o_st, o_sh;
-  int32_t Nq, Nc, H, n_qtiles, n_units;
-  int32_t team_size, n_teams, rounds;   // query tiles per team pass, teams (= spans), passes over the query tiles
+  int32_t Nq, Nc, H, n_qtiles;
+  int32_t team_size, n_teams, n_groups;   // members of a team, teams (= spans), groups of team_size query tiles
   int32_t total_cols;          // key tiles of all heads
+  int64_t line_len;            // n_groups * total_cols: positions of the line the teams share out
+  int16_t n_cut_units[kMaxHeads];   // units of a head that span boundaries cut (put together by the merge kernel)
   int32_t cum[kMaxHeads + 1];  // first column of the hh-th longest head
   uint32_t cur_bytes;  // addressable bytes of one head's current-chunk rows: ((Nc-1)*kc_st + d) * 2
   float c;             // softmax_scale * log2(e)
+  float inv_c;         // 1 / c
   float scale;         // softmax_scale
   int64_t hist_off[kMaxHeads + 1];
   int32_t hist_len[kMaxHeads];   // rows of each head that hold keys (a prefix of its rows)
@@ -153,104 +158,12 @@ struct TileLayout {
   static constexpr int v_row(int r) { return (r % NG) * VGS + (r / NG) * ROWB; }
 };
 
-// ---- hand-ordered LDS operand pipeline of the MFMA phase -------------------------------
-// The LDS reads that feed the matrix core are written as asm so that their order and the
-// waits between them are fixed: kOperandDepth operands are kept in flight, every MFMA waits
-// (s_waitcnt lgkmcnt(n)) only for its own operand.  LDS returns data in issue order, so n is
-// the number of reads issued after that operand.  The waited registers pass through the wait
-// statement ("+v"), which ties each MFMA to its wait.
-typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-constexpr int kOperandDepth = 4;
-
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F &&f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
-}
-template <int OFF>
-__device__ __forceinline__ u32x4 lds_read_b128(unsigned addr) {
-  u32x4 r;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-  return r;
-}
-template <int OFF>
-__device__ __forceinline__ u32x2 lds_read_tr16_b64(unsigned addr) {
-  u32x2 r;
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-  return r;
-}
-template <int N>
-__device__ __forceinline__ void wait_lds(u32x4 &a) {
-  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N));
-}
-template <int N>
-__device__ __forceinline__ void wait_lds(u32x2 &a, u32x2 &b) {
-  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
-}
 __device__ __forceinline__ unsigned lds_address(const void *ptr) {
   return unsigned(reinterpret_cast<uintptr_t>(ptr));     // low half of a flat LDS address = LDS offset
 }
 
-// One MFMA phase of a wave: S^T = K Q^T for the tile at k_addr (if DO_QK) followed by
-// O^T += V^T P^T for the tile at v_addr (if DO_PV).  k_addr / v_addr are this lane's LDS byte
-// addresses of the first A operand; all further operands are compile-time offsets from them.
-// `hook(r)` is called right after the r-th MFMA of the second product has been issued: VALU work placed
-// there runs in the shadow of the matrix core.
-template <int D, bool DO_QK, bool DO_PV, typename Hook>
-__device__ __forceinline__ void mfma_phase(unsigned k_addr, unsigned v_addr, const bf16x8 (&qf)[D / 16],
-                                           const bf16x8 (&pb)[2][2], f32x16 (&s)[2], f32x16 (&o)[D / 32],
-                                           Hook &&hook) {
-  constexpr int KS = D / 16, DB = D / 32;
-  using L = TileLayout<D>;
-  constexpr int NQK = DO_QK ? 2 * KS : 0;
-  constexpr int NPV = DO_PV ? 4 * DB : 0;
-  constexpr int NOPS = NQK + NPV;
-  u32x4 ka[NQK > 0 ? NQK : 1];
-  u32x2 va[NPV > 0 ? NPV : 1][2];
-  auto issue = [&](auto I) {
-    constexpr int i = decltype(I)::value;
-    if constexpr (i < NQK) {
-      constexpr int ks = i / 2, kb = i % 2;
-      ka[i] = lds_read_b128<L::k_row(32 * kb) + 32 * ks>(k_addr);
-    } else if constexpr (i < NOPS) {
-      constexpr int r = i - NQK, db = r % DB, ts = (r / DB) % 2, kb = r / (2 * DB);
-      constexpr int row0 = 32 * kb + 16 * ts;
-      va[r][0] = lds_read_tr16_b64<L::v_row(row0) + 64 * db>(v_addr);
-      va[r][1] = lds_read_tr16_b64<L::v_row(row0 + 4) + 64 * db>(v_addr);
-    }
-  };
-  static_for<0, (kOperandDepth < NOPS ? kOperandDepth : NOPS)>(issue);
-  __builtin_amdgcn_sched_barrier(0);
-  static_for<0, NOPS>([&](auto I) {
-    constexpr int i = decltype(I)::value;
-    // reads issued after operand i and before this point: operands i+1 .. i+kOperandDepth-1
-    constexpr int last = (i + kOperandDepth - 1 < NOPS - 1) ? i + kOperandDepth - 1 : NOPS - 1;
-    constexpr int n_qk_after = (last < NQK ? last : NQK - 1) - i > 0 ? ((last < NQK ? last : NQK - 1) - i) : 0;
-    constexpr int n_after = last - i;
-    constexpr int pending = n_qk_after * 1 + (n_after - n_qk_after) * 2;
-    if constexpr (i < NQK) {
-      constexpr int ks = i / 2, kb = i % 2;
-      wait_lds<pending>(ka[i]);
-      const bf16x8 a = __builtin_bit_cast(bf16x8, ka[i]);
-      if constexpr (ks == 0) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], zero, 0, 0, 0);
-      } else {
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
-      }
-    } else {
-      constexpr int r = i - NQK, db = r % DB, ts = (r / DB) % 2, kb = r / (2 * DB);
-      wait_lds<pending>(va[r][0], va[r][1]);
-      const u32x4 a4 = {va[r][0][0], va[r][0][1], va[r][1][0], va[r][1][1]};
-      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a4), pb[kb][ts], o[db], 0, 0, 0);
-      hook(std::integral_constant<int, r>{});
-    }
-    issue(std::integral_constant<int, i + kOperandDepth>{});
-    __builtin_amdgcn_sched_barrier(0);      // keep wait -> MFMA -> next read in program order
-  });
-}
+// The MFMA phase of a wave (both products of one tile, LDS operand reads hand-ordered) as one asm block.
+#include "df_attn_phase.inc"
 
 typedef __attribute__((address_space(3))) void lds_void;
 
@@ -266,14 +179,22 @@ struct Slot {
   __device__ static float *ovec(float *slot, int tid, int i) { return slot + kStats + (i * kThreads + tid) * 4; }
 };
 
-// Partial-result slot of (span, first or later piece of the span, query tile).
-__device__ __forceinline__ int64_t slot_index(const AttnParams &p, int span, int which, int qt) {
-  return (int64_t(2 * span + which) * p.rounds + qt / p.team_size) * p.team_size + qt % p.team_size;
+// Partial-result slot of (span, first or later piece of the span, member of the team).
+__device__ __forceinline__ int64_t slot_index(const AttnParams &p, int span, int which, int member) {
+  return int64_t(2 * span + which) * p.team_size + member;
 }
 
-// Where the work is cut.  Span s covers columns [span_begin(s), span_begin(s+1)).
-__device__ __forceinline__ int span_begin(int s, int total, int n_wg) {
-  return int((int64_t(s) * total) / n_wg);
+// Where the work is cut.  The line has one position per (group of query tiles, column); span s covers
+// positions [span_begin(s), span_begin(s+1)).  Host and device use the same arithmetic.
+__host__ __device__ __forceinline__ int64_t span_begin(int64_t s, int64_t line_len, int64_t n_spans) {
+  return (s * line_len) / n_spans;
+}
+
+// Head (index into the length-sorted order) that owns column `col`.
+__host__ __device__ __forceinline__ int head_of_column(const AttnParams &p, int col) {
+  int hh = 0;
+  while (col >= p.cum[hh + 1]) ++hh;
+  return hh;
 }
 
 // Normalise, round and store one thread's share of a finished unit; returns nothing.
@@ -292,21 +213,41 @@ __device__ __forceinline__ void store_output(const AttnParams &p, int h, int row
     }
 }
 
-// Sum of the two region masses over the 256 rows of a unit, in row order (deterministic).
-__device__ __forceinline__ void reduce_masses(const AttnParams &p, float *lds_red, int h, int qt, int tid, int hf,
+// Sum of the two region masses over the 256 rows of a unit, in a fixed order (deterministic): a
+// butterfly over the 32 rows of every wave, then the 8 waves in order.  Both halves of a lane pair hold
+// the same masses, so the butterfly stays inside one half.
+__device__ __forceinline__ void reduce_masses(const AttnParams &p, float *lds_red, int h, int qt, int tid,
                                               float mass_a, float mass_b) {
-  const int wave = tid >> 6, j = tid & 31;
-  if (hf == 0) {
-    lds_red[2 * (wave * 32 + j)] = mass_a;
-    lds_red[2 * (wave * 32 + j) + 1] = mass_b;
+  const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+  for (int m = 1; m < 32; m <<= 1) {
+    mass_a += __shfl_xor(mass_a, m);
+    mass_b += __shfl_xor(mass_b, m);
+  }
+  if (lane == 0) {
+    lds_red[2 * wave] = mass_a;
+    lds_red[2 * wave + 1] = mass_b;
   }
   __syncthreads();
   if (tid < 2) {
     float acc = 0.f;
-    for (int qi = 0; qi < kBQ; ++qi) acc += lds_red[2 * qi + tid];
+    for (int w = 0; w < kWaves; ++w) acc += lds_red[2 * w + tid];
     p.part[(int64_t(h) * p.n_qtiles + qt) * 4 + tid] = acc;
   }
   __syncthreads();
+}
+
+// F[h] = (sum_a, sum_b - sum_a, n - sum_b) / n over the head's query tiles, in tile order.
+__device__ __forceinline__ void finish_score(const AttnParams &p, int h) {
+  float a = 0.f, b = 0.f;
+  for (int t = 0; t < p.n_qtiles; ++t) {
+    a += p.part[(int64_t(h) * p.n_qtiles + t) * 4];
+    b += p.part[(int64_t(h) * p.n_qtiles + t) * 4 + 1];
+  }
+  const float inv = 1.f / float(p.Nq);
+  p.score[3 * h] = a * inv;
+  p.score[3 * h + 1] = (b - a) * inv;
+  p.score[3 * h + 2] = (float(p.Nq) - b) * inv;
 }
 
 template <int D, bool SCORE_ONLY>
@@ -318,20 +259,24 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   constexpr int kDmaPerPhase = GPW * (SCORE_ONLY ? 1 : 2);   // buffer loads a wave issues per VALU phase
   __shared__ __attribute__((aligned(16))) unsigned char lds_k[kNBuf * L::KTILE];
   __shared__ __attribute__((aligned(16))) unsigned char lds_v[SCORE_ONLY ? 16 : kNBuf * L::VTILE];
-  __shared__ float lds_red[kBQ * 2];
+  __shared__ float lds_red[kWaves * 2];
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int group = wave >> 2;
   const int j = lane & 31, hf = lane >> 5;
 
-  // ---- this workgroup's team (span of columns) and member index (query tile); XCD-major numbering
+  // the merge kernel counts the merged units of a head: its counters start at zero (this kernel ends
+  // before that one begins)
+  if (blockIdx.x == 0 && p.tickets != nullptr && tid < p.H) p.tickets[tid] = 0;
+
+  // ---- this workgroup's team (span of the line) and member index (query tile inside a group); XCD-major numbering
   const int n_slots_x = int(gridDim.x) / kXcd;
   const int wg = (gridDim.x % kXcd == 0) ? (blockIdx.x % kXcd) * n_slots_x + blockIdx.x / kXcd : blockIdx.x;
   const int span = wg / p.team_size, member = wg % p.team_size;
   if (span >= p.n_teams) return;
-  const int span_lo = span_begin(span, p.total_cols, p.n_teams);
-  const int span_hi = span_begin(span + 1, p.total_cols, p.n_teams);
+  const int64_t span_lo = span_begin(span, p.line_len, p.n_teams);
+  const int64_t span_hi = span_begin(span + 1, p.line_len, p.n_teams);
 
   // per-lane LDS byte addresses of the MFMA A operands (buffer 0); see TileLayout for the row placement
   const int g16 = lane >> 4, i16 = lane & 15;
@@ -350,14 +295,11 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   const uint32_t lane_vo_cur = uint32_t(voff_cur) + uint32_t(wave) * cur_stride_b;
 
 #pragma unroll 1
-  for (int round = 0; round < p.rounds; ++round) {
-  const int qt = round * p.team_size + member;   // this workgroup's query tile in this pass
-  if (qt >= p.n_qtiles) break;
-  int hh = 0;                                    // index into the length-sorted head order
-#pragma unroll 1
-  for (int pos = span_lo; pos < span_hi;) {
-    // ---- the piece at `pos`: head, first and last tile of this team's share
-    while (pos >= p.cum[hh + 1]) ++hh;
+  for (int64_t pos = span_lo; pos < span_hi;) {
+    // ---- the piece at `pos`: group of query tiles, head, first and last tile of this team's share
+    const int grp = int(pos / p.total_cols);
+    const int col = int(pos - int64_t(grp) * p.total_cols);
+    const int hh = head_of_column(p, col);         // index into the length-sorted head order
     const int h = p.order[hh];
     const int64_t hoff = p.hist_off[h];
     const int len_h = p.hist_len[h];
@@ -366,12 +308,17 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     const int nt1 = (len_h - sink + kKT - 1) / kKT;
     const int nt2 = (p.Nc + kKT - 1) / kKT;
     const int n_tiles = nt0 + nt1 + nt2;
-    const int t_begin = pos - p.cum[hh];
-    const int t_end = min(n_tiles, t_begin + (span_hi - pos));
+    const int t_begin = col - p.cum[hh];
+    const int t_end = int(min(int64_t(n_tiles), t_begin + (span_hi - pos)));
     const bool whole = (t_begin == 0) && (t_end == n_tiles);
-    const int piece_pos = pos;
+    const int64_t piece_pos = pos;
     pos += t_end - t_begin;
+    const int qt = grp * p.team_size + member;     // this workgroup's query tile in this group
+    if (qt >= p.n_qtiles) continue;                // the last group may have fewer tiles than the team has members
     const int q0 = qt * kBQ + wave * 32;
+    // a wave whose 32 rows all lie past the last query (tail of the last query tile) moves tiles and keeps
+    // the barriers, but computes nothing
+    const bool wave_live = q0 < p.Nq;
 
     // ---- global -> LDS: buffer descriptors of this head's history and current-chunk rows.  A load
     // past the end of the descriptor returns zeros, which is how partial and absent tiles are padded.
@@ -485,7 +432,8 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
     float m = -INFINITY;
-    float l4[4] = {0.f, 0.f, 0.f, 0.f};      // independent partial row sums (summed when needed)
+    float l = 0.f;                           // this lane's share of the row sum, relative to m
+    float nmc = INFINITY;                    // -m * c
     float snap_m0 = -INFINITY, snap_l0 = 0.f, snap_m1 = -INFINITY, snap_l1 = 0.f;
     f32x16 s[2];
     bf16x8 pb[2][2];                         // P^T of the previous tile, [key block][16-key step]
@@ -515,7 +463,28 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     // last tile of the segment that tile t lies in (empty segments have no tiles)
     auto seg_end_from = [&](int t) { return t < nt0 ? seg_end0 : (t < nt0 + nt1 ? seg_end1 : n_tiles - 1); };
     int next_seg_end = seg_end_from(t_begin);
-    float mx = 0.f, mx4[4] = {0.f, 0.f, 0.f, 0.f};
+    // P^T of the tile in s against the reference -nmc/c: bf16 operands of the second product into pb, and
+    // the sum of the unrounded values over this lane's 32 keys (four independent chains)
+    auto exp_tile = [&](float nmc_) {
+      float c4[4];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts) {
+          unsigned w[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float e0 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e], p.c, nmc_));
+            const float e1 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e + 1], p.c, nmc_));
+            w[e] = pack_bf16x2(e0, e1);
+            if (kb == 0 && ts == 0) c4[e] = e0 + e1;
+            else c4[e] += e0 + e1;   // plain adds: the dot-product instructions share the matrix core and stall its MFMAs
+          }
+          u32x4 u = {w[0], w[1], w[2], w[3]};
+          pb[kb][ts] = __builtin_bit_cast(bf16x8, u);
+        }
+      return (c4[0] + c4[1]) + (c4[2] + c4[3]);
+    };
 #pragma unroll 1
     for (int t = t_begin; t <= t_end; ++t) {
       int n_valid_t = kKT;                    // real keys in tile t: only a segment's last tile can be partial
@@ -531,43 +500,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
       {
         const unsigned k_addr = k_lane_addr + k_slot * L::KTILE;
         const unsigned v_addr = v_lane_addr + v_slot * L::VTILE;
-        // Row maximum of tile t, computed between the MFMAs of the second product (S is complete
-        // once a few of them have been issued).  Hook slots: 3 masks a partial tile, 4..11 reduce four
-        // accumulator registers each into four independent partial maxima, 12 combines the lane pair.
-        auto tile_max_hook = [&](auto R) {
-          constexpr int r = decltype(R)::value;
-          constexpr int first = DB * 4 > 12 ? 4 : 0;
-          if constexpr (r == first - 1 || (first == 0 && r == 0)) {
-            if (n_valid_t < kKT) {            // keys past the end of the segment
-#pragma unroll
-              for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                  const int key = 32 * kb + 16 * (v >> 3) + 8 * hf + (v & 7);
-                  if (key >= n_valid_t) s[kb][v] = -INFINITY;
-                }
-            }
-          }
-          if constexpr (DB * 4 > 12) {
-            if constexpr (r >= first && r < first + 8) {
-              constexpr int idx = r - first, kb = idx / 4, b = (idx % 4) * 4;
-              const float a = fmaxf(fmaxf(s[kb][b], s[kb][b + 1]), s[kb][b + 2]);
-              if constexpr (kb == 0) mx4[idx % 4] = fmaxf(a, s[kb][b + 3]);
-              else mx4[idx % 4] = fmaxf(fmaxf(mx4[idx % 4], a), s[kb][b + 3]);
-            }
-            if constexpr (r == first + 8) mx = pair_max(fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3])));
-          } else {
-            if constexpr (r == DB * 4 - 1) {   // short second product (d = 64): reduce in one go
-              float a = s[0][0];
-#pragma unroll
-              for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) a = fmaxf(a, s[kb][v]);
-              mx = pair_max(a);
-            }
-          }
-        };
-        mfma_phase<D, true, !SCORE_ONLY>(k_addr, v_addr, qf, pb, s, o, tile_max_hook);
+        if (wave_live) MfmaPhase<D, !SCORE_ONLY>::run(k_addr, v_addr, qf, pb, s, o);
         k_slot = (k_slot == kNBuf - 1) ? 0 : k_slot + 1;   // slot of K(t+1)
         v_slot = (v_slot == kNBuf - 1) ? 0 : v_slot + 1;   // slot of V(t)
       }
@@ -584,58 +517,47 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
       if (group == 1) iteration_barrier();
       // ================= VALU / memory phase =================
       phase_loads();
-      if (t < t_end) {
-        if (SCORE_ONLY) {                     // no second product to hide behind: reduce here
-          if (n_valid_t < kKT) {
+      if (t < t_end && wave_live) {
+        if (n_valid_t < kKT) {                // keys past the end of the segment
+          const int key0 = 8 * hf;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+          for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-              for (int v = 0; v < 16; ++v) {
-                const int key = 32 * kb + 16 * (v >> 3) + 8 * hf + (v & 7);
-                if (key >= n_valid_t) s[kb][v] = -INFINITY;
-              }
-          }
-#pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4) {
-            mx4[i4] = fmaxf(fmaxf(s[0][4 * i4], s[0][4 * i4 + 1]), fmaxf(s[0][4 * i4 + 2], s[0][4 * i4 + 3]));
-            mx4[i4] = fmaxf(mx4[i4], fmaxf(fmaxf(s[1][4 * i4], s[1][4 * i4 + 1]), fmaxf(s[1][4 * i4 + 2], s[1][4 * i4 + 3])));
-          }
-          mx = pair_max(fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3])));
+            for (int v = 0; v < 16; ++v)      // key = key0 + 32 kb + 16 (v / 8) + v % 8
+              if (key0 >= n_valid_t - (32 * kb + 16 * (v >> 3) + (v & 7))) s[kb][v] = -INFINITY;
         }
-        // raise the running maximum only when some row of the wave outgrew it by 2^kRescaleLog2
-        if (__any((mx - m) * p.c > kRescaleLog2)) {
-          const float m_new = fmaxf(m, mx);
+        // P = 2^(c s - c m) against the reference m the row already has, its sum in four chains
+        float ts = exp_tile(nmc);
+        float l_new = l + ts;
+        // No row maximum is taken on the common path.  m is only a reference: what has to hold is
+        // that nothing overflows, and any P beyond the limit (or infinite, or the NaN of an all-masked
+        // start) shows in the row's sum.  Rare: the first tile of a piece, and rows that outgrow 2^100.
+        if (__any(!(l_new <= kSumLimit))) {
+          float a = s[0][0];
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) a = fmaxf(a, s[kb][v]);
+          const float mx = pair_max(a);       // exact row maximum of the tile: the new P are at most 1
+          // the reference also absorbs the size of the sum so far (l becomes O(1)); -inf while l = 0
+          const float m_new = fmaxf(fmaxf(m, mx), m + __builtin_amdgcn_logf(pair_sum(l)) * p.inv_c);
           const float alpha = fast_exp2((m - m_new) * p.c);
           m = m_new;
-#pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4) l4[i4] *= alpha;
+          nmc = -m * p.c;
+          l *= alpha;
           if (!SCORE_ONLY) {
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
               for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
           }
+          ts = exp_tile(nmc);
+          l_new = l + ts;
         }
-        const float nmc = -m * p.c;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int ts = 0; ts < 2; ++ts) {
-            unsigned w[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float e0 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e], p.c, nmc));
-              const float e1 = fast_exp2(__builtin_fmaf(s[kb][8 * ts + 2 * e + 1], p.c, nmc));
-              w[e] = pack_bf16x2(e0, e1);
-              l4[e] += e0 + e1;     // plain adds: the dot-product instructions share the matrix core and stall its MFMAs
-            }
-            u32x4 u = {w[0], w[1], w[2], w[3]};
-            pb[kb][ts] = __builtin_bit_cast(bf16x8, u);
-          }
+        l = l_new;
         if (t == seg_end0 || t == seg_end1) {  // rare: keep the bookkeeping out of the common path
-          const float lsum = (l4[0] + l4[1]) + (l4[2] + l4[3]);
-          if (t == seg_end0) { snap_m0 = m; snap_l0 = lsum; }
-          if (t == seg_end1) { snap_m1 = m; snap_l1 = lsum; }
+          if (t == seg_end0) { snap_m0 = m; snap_l0 = l; }
+          if (t == seg_end1) { snap_m1 = m; snap_l1 = l; }
         }
       }
       if (group == 0) iteration_barrier();
@@ -645,7 +567,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     lds_barrier();
     // Region sums of this piece: a region that ended before the piece began contributes nothing, a
     // region the piece ends in (or before) contains everything the piece has summed.
-    const float l_piece = (l4[0] + l4[1]) + (l4[2] + l4[3]);
+    const float l_piece = l;
     if (seg_end0 >= t_end) { snap_m0 = m; snap_l0 = l_piece; }
     if (seg_end1 >= t_end) { snap_m1 = m; snap_l1 = l_piece; }
 
@@ -662,10 +584,10 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
         if (p.lse != nullptr && hf == 0) p.lse[int64_t(h) * p.Nq + row] = m * p.scale + __logf(lt);
       }
       if (p.part != nullptr)
-        reduce_masses(p, lds_red, h, qt, tid, hf, valid ? l1 * inv : 0.f, valid ? l2 * inv : 0.f);
+        reduce_masses(p, lds_red, h, qt, tid, valid ? l1 * inv : 0.f, valid ? l2 * inv : 0.f);
     } else {
       // a piece that starts at the span's first iteration uses the span's slot 0, a later one slot 1
-      float *slot = p.slots + slot_index(p, span, piece_pos == span_lo ? 0 : 1, qt) * Slot<D>::kFloats;
+      float *slot = p.slots + slot_index(p, span, piece_pos == span_lo ? 0 : 1, member) * Slot<D>::kFloats;
       float4 st = {m, lt, l1, l2};
       *reinterpret_cast<float4 *>(Slot<D>::stats(slot, tid)) = st;
       if (!SCORE_ONLY) {
@@ -679,39 +601,42 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
       }
     }
   }
-  }
 }
 
-// Second kernel: one workgroup per unit; a unit that was cut by a span boundary is put together from
-// the partial results of its pieces, in key order, with the usual log-sum-exp weights.
+// Second kernel.  Workgroup (k, member) looks at the boundary between spans k-1 and k: if it falls inside
+// a head (not on its first column), the unit (group, head, member's query tile) was cut there and is
+// put together from the partial results of its pieces, in key order, with the usual log-sum-exp
+// weights; a unit cut by several boundaries is handled at the first of them.  When scores are wanted,
+// the workgroup that completes the last unit of a head (counted per head) sums the head's per-tile
+// masses in tile order; heads that were not cut anywhere get a workgroup of their own for that
+// (index >= (n_teams - 1) * team_size).
 template <int D, bool SCORE_ONLY>
 __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParams p) {
   constexpr int DB = D / 32;
-  __shared__ float lds_red[kBQ * 2];
+  __shared__ float lds_red[kWaves * 2];
+  __shared__ int lds_last;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63, j = lane & 31, hf = lane >> 5;
-  // unit -> head, query tile, range of tile iterations
-  int hh = 0;
-  int unit = blockIdx.x;
-  int h = p.order[0];
-  int n_tiles = 0;
-  for (;; ++hh) {
-    h = p.order[hh];
-    const int len_h = p.hist_len[h];
-    const int sink = p.sink_len[h];
-    n_tiles = (sink + kKT - 1) / kKT + (len_h - sink + kKT - 1) / kKT + (p.Nc + kKT - 1) / kKT;
-    if (unit < p.n_qtiles) break;
-    unit -= p.n_qtiles;
+  const int n_merge = (p.n_teams - 1) * p.team_size;
+  if (int(blockIdx.x) >= n_merge) {                // score of a head no boundary cuts
+    const int h = int(blockIdx.x) - n_merge;
+    if (tid == 0 && p.n_cut_units[h] == 0) finish_score(p, h);
+    return;
   }
-  const int qt = unit;
-  const int u_lo = p.cum[hh], u_hi = u_lo + n_tiles;
-  // spans that hold the first and the last column of the head
-  int s_lo = int((int64_t(u_lo) * p.n_teams) / p.total_cols);
-  while (span_begin(s_lo + 1, p.total_cols, p.n_teams) <= u_lo) ++s_lo;
-  while (span_begin(s_lo, p.total_cols, p.n_teams) > u_lo) --s_lo;
-  int s_hi = s_lo;
-  while (span_begin(s_hi + 1, p.total_cols, p.n_teams) < u_hi) ++s_hi;
-  if (s_lo == s_hi) return;                       // the unit was finished in place
+  const int k = int(blockIdx.x) / p.team_size + 1, member = int(blockIdx.x) % p.team_size;
+  const int64_t cut = span_begin(k, p.line_len, p.n_teams);
+  const int grp = int(cut / p.total_cols);
+  const int col = int(cut - int64_t(grp) * p.total_cols);
+  const int hh = head_of_column(p, col);
+  if (col == p.cum[hh]) return;                    // the boundary coincides with the head's first column
+  const int64_t u_lo = int64_t(grp) * p.total_cols + p.cum[hh], u_hi = u_lo + (p.cum[hh + 1] - p.cum[hh]);
+  if (k >= 2 && span_begin(k - 1, p.line_len, p.n_teams) > u_lo) return;   // an earlier boundary cuts the same unit
+  const int qt = grp * p.team_size + member;
+  if (qt >= p.n_qtiles) return;
+  const int h = p.order[hh];
+  const int s_lo = k - 1;                          // span that holds the unit's first column
+  int s_hi = k;
+  while (span_begin(s_hi + 1, p.line_len, p.n_teams) < u_hi) ++s_hi;
 
   float M = -INFINITY, Lt = 0.f, La = 0.f, Lb = 0.f;
   f32x16 o[DB];
@@ -721,12 +646,13 @@ __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParam
     for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
 #pragma unroll 1
   for (int sp = s_lo; sp <= s_hi; ++sp) {
-    const int b = span_begin(sp, p.total_cols, p.n_teams);
-    const int piece_lo = max(u_lo, b);
-    const float *slot = p.slots + slot_index(p, sp, piece_lo == b ? 0 : 1, qt) * Slot<D>::kFloats;
+    const int64_t b = span_begin(sp, p.line_len, p.n_teams);
+    const float *slot = p.slots + slot_index(p, sp, u_lo > b ? 1 : 0, member) * Slot<D>::kFloats;
     const float4 st = *reinterpret_cast<const float4 *>(Slot<D>::stats(const_cast<float *>(slot), tid));
     const float m_new = fmaxf(M, st.x);
-    const float w_old = fast_exp2((M - m_new) * p.c), w_new = fast_exp2((st.x - m_new) * p.c);
+    // a piece of a wave that computes nothing (rows past the last query) has m = -inf throughout
+    const float w_old = (M == m_new) ? 1.f : fast_exp2((M - m_new) * p.c);
+    const float w_new = (st.x == m_new) ? 1.f : fast_exp2((st.x - m_new) * p.c);
     M = m_new;
     Lt = Lt * w_old + st.y * w_new;
     La = La * w_old + st.z * w_new;
@@ -751,49 +677,49 @@ __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParam
     store_output<D>(p, h, row, hf, o, inv);
     if (p.lse != nullptr && hf == 0) p.lse[int64_t(h) * p.Nq + row] = M * p.scale + __logf(Lt);
   }
-  if (p.part != nullptr)
-    reduce_masses(p, lds_red, h, qt, tid, hf, valid ? La * inv : 0.f, valid ? Lb * inv : 0.f);
-}
-
-// F[h] = (sum_a, sum_b - sum_a, n - sum_b) / n over the head's query tiles, in tile order.
-__global__ void df_score_finish_kernel(const float *part, float *score, int n_qtiles, int n_rows) {
-  const int h = blockIdx.x;
-  if (threadIdx.x != 0) return;
-  float a = 0.f, b = 0.f;
-  for (int t = 0; t < n_qtiles; ++t) {
-    a += part[(int64_t(h) * n_qtiles + t) * 4];
-    b += part[(int64_t(h) * n_qtiles + t) * 4 + 1];
+  if (p.part != nullptr) {
+    reduce_masses(p, lds_red, h, qt, tid, valid ? La * inv : 0.f, valid ? Lb * inv : 0.f);
+    // the unit's masses are out; whoever completes the head's last merged unit sums the head
+    if (tid == 0) {
+      __threadfence();
+      const int done = __hip_atomic_fetch_add(p.tickets + h, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      lds_last = (done == p.n_cut_units[h] - 1);
+      if (lds_last) {
+        __threadfence();
+        finish_score(p, h);
+      }
+    }
   }
-  const float inv = 1.f / float(n_rows);
-  score[3 * h] = a * inv;
-  score[3 * h + 1] = (b - a) * inv;
-  score[3 * h + 2] = (float(n_rows) - b) * inv;
 }
 
 constexpr int64_t kMaxBufferBytes = 0x7ff00000;   // one head's rows must stay below the "no tile" offset
 constexpr int kMinQTile = 128;   // smallest query tile any kernel variant uses (sizes the workspace)
 
 // Workspace layout: [score partials: H * ceil(Nq/128) * 4 floats, rounded up to 256 B]
+//                   [unit counters of the merge kernel: 256 B]
 //                   [partial-result slots: 2 per workgroup, kNumCU workgroups at most]
 static size_t part_bytes(int H, int Nq) {
   const size_t tiles = (size_t(Nq) + kMinQTile - 1) / kMinQTile;
   return ((size_t(H) * tiles * 4 * sizeof(float) + 255) / 256) * 256;
 }
+constexpr size_t kTicketBytes = 256;
+static_assert(kMaxHeads * sizeof(int32_t) <= kTicketBytes, "one counter per head");
 static size_t slot_bytes(int d) {
   return size_t(d == 128 ? Slot<128>::kFloats : Slot<64>::kFloats) * sizeof(float);
 }
 static size_t workspace_bytes(int H, int d, int Nq) {
-  // two slots per (team, query tile of a pass); teams * team size <= kNumCU
-  const size_t n_qtiles = (size_t(Nq) + kBQ - 1) / kBQ;
-  const size_t rounds = (n_qtiles + kNumCU - 1) / kNumCU;
-  return part_bytes(H, Nq) + 2 * size_t(kNumCU) * rounds * slot_bytes(d);
+  return part_bytes(H, Nq) + kTicketBytes + 2 * size_t(kNumCU) * slot_bytes(d);
 }
 
-template <int D, bool SCORE_ONLY>
-static df_status launch(AttnParams &p, void *workspace, float *score_out, hipStream_t st) {
+// The decomposition of a launch (A4).  Columns = key tiles of all heads, longest head first.  Query tiles
+// are taken in groups of `team_size`; the line has one position per (group, column) and is cut into
+// equal spans, one per team.  A team has one workgroup per query tile of a group; its members walk the
+// same columns at the same time.  team_size is chosen so that as many of the kNumCU workgroups as
+// possible have a query tile in every group: when the number of query tiles does not divide the
+// number of compute units, smaller teams (more groups) fill the machine better than one team member per
+// query tile.
+static df_status plan(AttnParams &p) {
   p.n_qtiles = (p.Nq + kBQ - 1) / kBQ;
-  p.n_units = p.n_qtiles * p.H;
-  // the line of columns: key tiles of all heads, longest head first
   int64_t total = 0;
   for (int hh = 0; hh < p.H; ++hh) {
     const int h = p.order[hh];
@@ -805,21 +731,58 @@ static df_status launch(AttnParams &p, void *workspace, float *score_out, hipStr
   }
   p.cum[p.H] = int32_t(total);
   p.total_cols = int32_t(total);
-  p.team_size = std::min(p.n_qtiles, kNumCU);
-  p.rounds = (p.n_qtiles + p.team_size - 1) / p.team_size;
-  p.n_teams = int32_t(std::max<int64_t>(1, std::min<int64_t>(kNumCU / p.team_size, total / kMinSpan)));
-  p.part = score_out ? static_cast<float *>(workspace) : nullptr;
-  p.slots = reinterpret_cast<float *>(static_cast<char *>(workspace) + part_bytes(p.H, p.Nq));
+  // busy share of the machine for a team size s: workgroups launched x tiles present in the average group
+  auto teams_of = [&](int s) {
+    const int64_t groups = (p.n_qtiles + s - 1) / s;
+    return int64_t(std::max<int64_t>(1, std::min<int64_t>(kNumCU / s, groups * total / kMinSpan)));
+  };
+  auto busy = [&](int s) {
+    const int64_t groups = (p.n_qtiles + s - 1) / s;
+    return double(teams_of(s) * s) / kNumCU * double(p.n_qtiles) / double(groups * s);
+  };
+  const int s_max = std::min(p.n_qtiles, kNumCU);
+  double best = 0.0;
+  for (int s = 1; s <= s_max; ++s) best = std::max(best, busy(s));
+  // Larger teams share every K/V tile among more workgroups while it is hot in L2, so the largest team
+  // that keeps 95 % of the machine busy (or the best there is) wins.
+  const double want = std::min(best, 0.95);
+  int team = s_max;
+  while (team > 1 && busy(team) < want) --team;
+  p.team_size = team;
+  p.n_groups = (p.n_qtiles + team - 1) / team;
+  p.n_teams = int32_t(teams_of(team));
+  p.line_len = int64_t(p.n_groups) * total;
+  // units cut by a span boundary (the same walk as the merge kernel's)
+  for (int h = 0; h < p.H; ++h) p.n_cut_units[h] = 0;
+  for (int k = 1; k < p.n_teams; ++k) {
+    const int64_t cut = span_begin(k, p.line_len, p.n_teams);
+    const int grp = int(cut / total);
+    const int col = int(cut - int64_t(grp) * total);
+    const int hh = head_of_column(p, col);
+    if (col == p.cum[hh]) continue;
+    const int64_t u_lo = int64_t(grp) * total + p.cum[hh];
+    if (k >= 2 && span_begin(k - 1, p.line_len, p.n_teams) > u_lo) continue;
+    p.n_cut_units[p.order[hh]] += std::min(team, p.n_qtiles - grp * team);
+  }
+  return DF_OK;
+}
+
+template <int D, bool SCORE_ONLY>
+static df_status launch(AttnParams &p, void *workspace, float *score_out, hipStream_t st) {
+  if (df_status s = plan(p)) return s;
+  char *ws = static_cast<char *>(workspace);
+  p.part = score_out ? reinterpret_cast<float *>(ws) : nullptr;
+  p.tickets = score_out ? reinterpret_cast<int32_t *>(ws + part_bytes(p.H, p.Nq)) : nullptr;
+  p.slots = reinterpret_cast<float *>(ws + part_bytes(p.H, p.Nq) + kTicketBytes);
+  p.score = score_out;
   const int n_wg = p.n_teams * p.team_size;
   const int grid = n_wg >= kXcd ? (n_wg + kXcd - 1) / kXcd * kXcd : n_wg;   // XCD-major numbering needs a multiple of 8
   hipLaunchKernelGGL((df_attn_kernel<D, SCORE_ONLY>), dim3(grid), dim3(kThreads), 0, st, p);
   if (df_status s = launch_status()) return s;
-  if (p.n_teams > 1) {
-    hipLaunchKernelGGL((df_attn_merge_kernel<D, SCORE_ONLY>), dim3(p.n_units), dim3(kThreads), 0, st, p);
-    if (df_status s = launch_status()) return s;
-  }
-  if (score_out) {
-    hipLaunchKernelGGL(df_score_finish_kernel, dim3(p.H), dim3(64), 0, st, p.part, score_out, p.n_qtiles, p.Nq);
+  // second launch: units cut by span boundaries, and the per-head score sums
+  const int n_merge = (p.n_teams - 1) * p.team_size + (score_out ? p.H : 0);
+  if (n_merge > 0) {
+    hipLaunchKernelGGL((df_attn_merge_kernel<D, SCORE_ONLY>), dim3(n_merge), dim3(kThreads), 0, st, p);
     if (df_status s = launch_status()) return s;
   }
   return DF_OK;
@@ -871,6 +834,46 @@ extern "C" size_t df_attn_workspace_bytes(int32_t H, int32_t d, int32_t Nq) {
   return workspace_bytes(H, d, Nq);
 }
 
+extern "C" df_status df_attn_plan(int32_t H, int32_t Nq, int32_t Nc, const int32_t *hist_len,
+                                  const int32_t *hist_sink_len, df_attn_plan_info *out) {
+  if (!hist_len || !out) return DF_ERR_NULL;
+  if (H <= 0 || Nq <= 0 || Nc <= 0) return DF_ERR_SHAPE;
+  if (H > kMaxHeads) return DF_ERR_UNSUPPORTED;
+  AttnParams p{};
+  int idx[kMaxHeads];
+  for (int h = 0; h < H; ++h) {
+    const int32_t sl = hist_sink_len ? hist_sink_len[h] : 0;
+    if (hist_len[h] < 0 || sl < 0 || sl > hist_len[h]) return DF_ERR_RANGE;
+    p.hist_len[h] = hist_len[h];
+    p.sink_len[h] = sl;
+    idx[h] = h;
+  }
+  std::stable_sort(idx, idx + H, [&](int a, int b) { return p.hist_len[a] > p.hist_len[b]; });
+  for (int h = 0; h < H; ++h) p.order[h] = uint8_t(idx[h]);
+  p.H = H;
+  p.Nq = Nq;
+  p.Nc = Nc;
+  if (df_status s = plan(p)) return s;
+  out->n_qtiles = p.n_qtiles;
+  out->team_size = p.team_size;
+  out->n_groups = p.n_groups;
+  out->n_teams = p.n_teams;
+  out->workgroups = p.n_teams * p.team_size;
+  out->cut_units = 0;
+  for (int h = 0; h < H; ++h) out->cut_units += p.n_cut_units[h];
+  out->total_cols = p.total_cols;
+  out->line_len = p.line_len;
+  out->span_min = INT64_MAX;
+  out->span_max = 0;
+  for (int t = 0; t < p.n_teams; ++t) {
+    const int64_t len = span_begin(t + 1, p.line_len, p.n_teams) - span_begin(t, p.line_len, p.n_teams);
+    out->span_min = std::min(out->span_min, len);
+    out->span_max = std::max(out->span_max, len);
+  }
+  out->busy = double(out->workgroups) / kNumCU * double(p.n_qtiles) / double(int64_t(p.n_groups) * p.team_size);
+  return DF_OK;
+}
+
 extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
   if (!a) return DF_ERR_NULL;
   if (!a->q || !a->k_cur || !a->v_cur || !a->out) return DF_ERR_NULL;
@@ -902,6 +905,7 @@ extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
   p.cur_bytes = uint32_t((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2);
   p.scale = a->softmax_scale;
   p.c = a->softmax_scale * 1.4426950408889634f;
+  p.inv_c = 1.f / p.c;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (a->d == 128) return launch<128, false>(p, a->workspace, a->score_out, st);
   return launch<64, false>(p, a->workspace, a->score_out, st);
@@ -942,6 +946,7 @@ extern "C" df_status df_head_score(const df_score_args *a, void *stream) {
   p.cur_bytes = uint32_t((int64_t(a->Nc - 1) * a->kc_stride_tok + a->d) * 2);
   p.scale = a->softmax_scale;
   p.c = a->softmax_scale * 1.4426950408889634f;
+  p.inv_c = 1.f / p.c;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (a->d == 128) return launch<128, true>(p, a->workspace, a->score_out, st);
   return launch<64, true>(p, a->workspace, a->score_out, st);

@@ -11,9 +11,9 @@ MEAN_ABS = 2e-3
 REL_L2 = 1e-2      # extra guard: i.i.d. values average out, so the absolute bar alone is loose
 F_ABS = 1e-4
 # log-sum-exp: m*scale (fp32, |m*scale| up to a few tens: 2^-24 relative) + ln of an fp32 sum of up to 4e5
-# hardware exp2 values (1 ulp each, summed in tile order) through the hardware log2: all of the order
-# of 1e-5; the bar leaves a factor of ten
-LSE_ABS = 5e-4
+# hardware exp2 values (1 ulp each, summed in tile order) through the hardware log2: a few 1e-6 (measured
+# 1.9e-6 at the Wan-shaped size over all rows); the bar leaves a factor of fifty
+LSE_ABS = 1e-4
 
 
 def dev():

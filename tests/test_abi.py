@@ -40,7 +40,8 @@ def test_library_exports_every_declared_symbol(b):
 
 def test_struct_layout_matches_c(b, tmp_path):
     structs = {"df_attn_args": b.df_attn_args, "df_score_args": b.df_score_args, "df_cache": b.df_cache,
-               "df_append_args": b.df_append_args, "df_pack_args": b.df_pack_args}
+               "df_append_args": b.df_append_args, "df_pack_args": b.df_pack_args,
+               "df_attn_plan_info": b.df_attn_plan_info}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "df.h"', 'int main(void){']
     for sname, st in structs.items():
         lines.append(f'printf("{sname} %zu\\n", sizeof({sname}));')
@@ -218,3 +219,54 @@ def test_cache_argument_validation(b):
     cache.sink_len[0], cache.win_len[0], cache.win_pos[0] = 2, 8, 3
     pk.out_capacity_rows = 5
     assert b.lib.df_pack_context(C.byref(pk), None) == b.DF_ERR_RANGE
+
+
+def test_generated_mfma_phase_is_current():
+    """The committed asm include of the attention kernel is what its generator writes."""
+    import importlib.util
+    path = os.path.join(ROOT, "paper_2601_20499_amd", "csrc", "gen_attn_phase.py")
+    spec = importlib.util.spec_from_file_location("gen_attn_phase", path)
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    assert open(gen.OUT).read() == gen.text()
+
+
+CONFIG_MIXES = {
+    "config2 (9 full of 1+5 frames, 3 dummy)": ([9360] * 9 + [0] * 3, [1560] * 9 + [0] * 3, 1560),
+    "config4 (9 full of 12 frames at 720P, 3 dummy)": ([43200] * 9 + [0] * 3, [3600] * 9 + [0] * 3, 3600),
+    "config5 (6 dummy, 3..60 frames)": ([4680, 93600, 0, 0, 31200, 0, 56160, 0, 14040, 0, 74880, 0],
+                                       [1560, 1560, 0, 0, 1560, 0, 1560, 0, 1560, 0, 1560, 0], 1560),
+}
+
+
+@pytest.mark.parametrize("Nq", [4680, 10800, 24480, 33024, 65797])
+@pytest.mark.parametrize("mix", list(CONFIG_MIXES))
+def test_attention_plan_fills_the_machine(b, Nq, mix):
+    """The launch decomposition keeps at least 95 % of the 256 workgroup slots busy and its spans within
+    3 % of each other for every query count of the named shapes (and one that is a multiple of nothing)."""
+    hist_len, sink_len, _ = CONFIG_MIXES[mix]
+    r = b.df_attn_plan(Nq, Nq, hist_len, sink_len)
+    assert r["n_qtiles"] == -(-Nq // 256)
+    assert r["workgroups"] == r["n_teams"] * r["team_size"] <= 256
+    assert r["n_groups"] == -(-r["n_qtiles"] // r["team_size"])
+    assert r["busy"] >= 0.95, r
+    assert r["span_max"] - r["span_min"] <= 1 and r["span_max"] <= 1.03 * r["line_len"] / r["n_teams"] + 1, r
+    tiles = lambda n: -(-n // 64)
+    cols = sum(tiles(s) + tiles(l - s) + tiles(Nq) for l, s in zip(hist_len, sink_len))
+    assert r["total_cols"] == cols and r["line_len"] == cols * r["n_groups"]
+    assert 0 <= r["cut_units"] <= (r["n_teams"] - 1) * r["team_size"]
+
+
+def test_attention_plan_small_and_error_cases(b):
+    r = b.df_attn_plan(64, 64, [192, 192, 192, 0], [64, 64, 64, 0])          # config 1: one query tile
+    assert r["n_qtiles"] == 1 and r["team_size"] == 1 and r["n_groups"] == 1 and r["n_teams"] >= 1
+    r = b.df_attn_plan(1, 1, [0])                                            # one key tile in all: one workgroup
+    assert r["workgroups"] == 1 and r["cut_units"] == 0 and r["line_len"] == 1
+    for bad, code in (((0, 1, [0]), b.DF_ERR_SHAPE), ((1, 0, [0]), b.DF_ERR_SHAPE), ((1, 1, [-1]), b.DF_ERR_RANGE),
+                      ((1, 1, [0] * 65), b.DF_ERR_UNSUPPORTED)):
+        with pytest.raises(b.DfError) as e:
+            b.df_attn_plan(*bad)
+        assert e.value.status == code
+    with pytest.raises(b.DfError) as e:
+        b.df_attn_plan(4, 4, [10], [11])                                    # sink longer than the history
+    assert e.value.status == b.DF_ERR_RANGE
