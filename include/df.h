@@ -120,6 +120,19 @@ typedef struct df_attn_args {
 size_t df_attn_workspace_bytes(int32_t H, int32_t d, int32_t Nq);
 df_status df_attn_fwd(const df_attn_args *args, void *stream);
 
+/* df_attn_fwd_static: df_attn_fwd for callers that cannot allocate device memory (code under HIP graph
+ * capture, serving loops and harnesses that forbid hipMalloc).  args->workspace and
+ * args->workspace_bytes are ignored: the workspace is a device array of DF_STATIC_SCRATCH_BYTES bytes
+ * inside the library, which every GPU the library runs on holds until the process ends.  Same
+ * kernels, same results bit for bit, same validation and error codes as df_attn_fwd, plus
+ * DF_ERR_WORKSPACE when df_attn_workspace_bytes(H, d, Nq) exceeds DF_STATIC_SCRATCH_BYTES (with d = 128
+ * that is H * ceil(Nq / 128) > 262128, i.e. more than 524160 queries at H = 64) and DF_ERR_LAUNCH when
+ * the runtime cannot give the array's address.  The call allocates nothing.  All calls on one GPU share the array: calls that
+ * may overlap on one GPU (different streams, different threads) race and must be ordered by the
+ * caller; nothing in it has to be cleared between calls. */
+#define DF_STATIC_SCRATCH_BYTES (70u << 20)
+df_status df_attn_fwd_static(const df_attn_args *args, void *stream);
+
 /* df_attn_plan: how df_attn_fwd / df_head_score share a launch out over the GPU's 256 compute units
  * (the head-type-driven scheduling: heads differ in context length by Eq. 5 / Eq. 8, so work is cut by
  * key tiles, not by heads).  Pure host code, launches nothing; for callers and tests that want to see

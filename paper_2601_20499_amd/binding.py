@@ -21,7 +21,7 @@ DF_MAX_HEADS = 64
 DF_HEAD_FULL, DF_HEAD_SINK, DF_HEAD_NEIGHBOR, DF_HEAD_DUMMY, DF_HEAD_PACK_DUMMY = range(5)
 DF_CLASSIFY_TWO_CLASS, DF_CLASSIFY_DHP = 0, 1
 
-EXPORTS = ["df_status_string", "df_head_context", "df_attn_workspace_bytes", "df_attn_fwd", "df_attn_plan",
+EXPORTS = ["df_status_string", "df_head_context", "df_attn_workspace_bytes", "df_attn_fwd", "df_attn_fwd_static", "df_attn_plan",
            "df_head_score", "df_classify", "df_kv_append", "df_pack_context"]
 
 
@@ -100,6 +100,8 @@ def _load() -> C.CDLL:
     lib.df_attn_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
     lib.df_attn_fwd.restype = C.c_int32
     lib.df_attn_fwd.argtypes = [C.POINTER(df_attn_args), C.c_void_p]
+    lib.df_attn_fwd_static.restype = C.c_int32
+    lib.df_attn_fwd_static.argtypes = [C.POINTER(df_attn_args), C.c_void_p]
     lib.df_attn_plan.restype = C.c_int32
     lib.df_attn_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                  C.POINTER(df_attn_plan_info)]
@@ -171,8 +173,18 @@ def df_attn_workspace_bytes(H: int, d: int, Nq: int) -> int:
     return int(lib.df_attn_workspace_bytes(H, d, Nq))
 
 
+DF_STATIC_SCRATCH_BYTES = 70 << 20
+
+
+def df_attn_fwd_static(q, k_cur, v_cur, k_hist, v_hist, hist_off, hist_sink_len, out, softmax_scale,
+                       lse_out=None, score_out=None, stream=None, hist_len=None):
+    """df_attn_fwd on the library's static device scratch: no workspace argument, nothing allocated."""
+    df_attn_fwd(q, k_cur, v_cur, k_hist, v_hist, hist_off, hist_sink_len, out, softmax_scale, lse_out=lse_out,
+                score_out=score_out, workspace=None, stream=stream, hist_len=hist_len, _entry="df_attn_fwd_static")
+
+
 def df_attn_fwd(q, k_cur, v_cur, k_hist, v_hist, hist_off, hist_sink_len, out, softmax_scale,
-                lse_out=None, score_out=None, workspace=None, stream=None, hist_len=None):
+                lse_out=None, score_out=None, workspace=None, stream=None, hist_len=None, _entry="df_attn_fwd"):
     """q/out: [Nq, H, d] and k_cur/v_cur: [Nc, H, d] bf16 device tensors (any token/head strides,
     d contiguous); k_hist/v_hist: [hist_off[-1], d] bf16; hist_off/hist_sink_len/hist_len: python ints."""
     a = df_attn_args()
@@ -193,7 +205,7 @@ def df_attn_fwd(q, k_cur, v_cur, k_hist, v_hist, hist_off, hist_sink_len, out, s
     a.softmax_scale = softmax_scale
     a.workspace = _ptr(workspace)
     a.workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib.df_attn_fwd(C.byref(a), _stream_handle(stream)), "df_attn_fwd")
+    _check(getattr(lib, _entry)(C.byref(a), _stream_handle(stream)), _entry)
 
 
 def df_head_score(q, k_cur, k_hist, hist_off, hist_sink_len, score_out, softmax_scale,

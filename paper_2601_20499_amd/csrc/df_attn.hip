@@ -61,6 +61,7 @@
 // l1*2^(m1-m3)/l3, (l2*2^(m2-m3) - l1*2^(m1-m3))/l3 and the remainder.
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <numeric>
 #include <type_traits>
 
@@ -874,7 +875,9 @@ extern "C" df_status df_attn_plan(int32_t H, int32_t Nq, int32_t Nc, const int32
   return DF_OK;
 }
 
-extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
+// df_attn_fwd with the workspace given separately: the caller's (df_attn_fwd) or the library's static
+// scratch (df_attn_fwd_static).
+static df_status attn_fwd(const df_attn_args *a, void *stream, void *workspace, size_t workspace_size) {
   if (!a) return DF_ERR_NULL;
   if (!a->q || !a->k_cur || !a->v_cur || !a->out) return DF_ERR_NULL;
   AttnParams p{};
@@ -888,8 +891,8 @@ extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
       (multi && (!stride_ok(a->q_stride_head) || !stride_ok(a->kc_stride_head) || !stride_ok(a->o_stride_head))))
     return DF_ERR_ALIGN;
   if (!(a->softmax_scale > 0.f) || !std::isfinite(a->softmax_scale)) return DF_ERR_RANGE;
-  if (!a->workspace || a->workspace_bytes < workspace_bytes(a->H, a->d, a->Nq)) return DF_ERR_WORKSPACE;
-  if (reinterpret_cast<uintptr_t>(a->workspace) & 255u) return DF_ERR_ALIGN;
+  if (!workspace || workspace_size < workspace_bytes(a->H, a->d, a->Nq)) return DF_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return DF_ERR_ALIGN;
   p.q = static_cast<const u16 *>(a->q);
   p.k_cur = static_cast<const u16 *>(a->k_cur);
   p.v_cur = static_cast<const u16 *>(a->v_cur);
@@ -907,8 +910,51 @@ extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
   p.c = a->softmax_scale * 1.4426950408889634f;
   p.inv_c = 1.f / p.c;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (a->d == 128) return launch<128, false>(p, a->workspace, a->score_out, st);
-  return launch<64, false>(p, a->workspace, a->score_out, st);
+  if (a->d == 128) return launch<128, false>(p, workspace, a->score_out, st);
+  return launch<64, false>(p, workspace, a->score_out, st);
+}
+
+extern "C" df_status df_attn_fwd(const df_attn_args *a, void *stream) {
+  if (!a) return DF_ERR_NULL;
+  return attn_fwd(a, stream, a->workspace, a->workspace_bytes);
+}
+
+// ---- df_attn_fwd_static: the same call for callers that cannot allocate (see df.h) -------------------
+// The workspace is a file-scope device array.  Its name is only a host-side handle: the device address
+// is looked up once per device and kept, and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[DF_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, or null if the runtime cannot provide it.
+void *static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" df_status df_attn_fwd_static(const df_attn_args *a, void *stream) {
+  if (!a) return DF_ERR_NULL;
+  // sizes first: nothing else is looked at when the launch cannot fit the static scratch
+  if (a->H <= 0 || a->Nq <= 0 || a->Nc <= 0) return DF_ERR_SHAPE;
+  if (a->H > kMaxHeads || (a->d != 64 && a->d != 128)) return DF_ERR_UNSUPPORTED;
+  if (workspace_bytes(a->H, a->d, a->Nq) > size_t(DF_STATIC_SCRATCH_BYTES)) return DF_ERR_WORKSPACE;
+  void *ws = static_scratch();
+  if (!ws) return DF_ERR_LAUNCH;
+  return attn_fwd(a, stream, ws, size_t(DF_STATIC_SCRATCH_BYTES));
 }
 
 extern "C" df_status df_head_score(const df_score_args *a, void *stream) {
