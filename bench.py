@@ -9,18 +9,29 @@ already resident in HBM:
     df_pack_context -> df_attn_fwd (with the fused frame attention score) -> df_kv_append
     [the per-chunk-layer path on the typed, heterogeneous cache].
 
-The classification must reproduce the workload's designated dummy heads (asserted).
+The classification must reproduce the workload's designated dummy heads (asserted).  In a real
+generation loop the head programming runs once per shot (Dynamic Head Programming paragraph,
+App. C) and the other three calls once per chunk-layer; the step times them all, the host
+classification is done on the copied scores after the timed GPU work (it is not on the per-step
+dependency chain).
 
-Prints ONE JSON line.  `value` is algorithmic TFLOP/s of the step (attention + scoring FLOP
-over visible keys only, divided by the step time); `roofline` describes the dominant kernel
-(the attention kernel) from HIP-event timings taken inside the timed region; `cpu_baseline`
-is the fp64 oracle timed on this machine's host cores on a bounded row sample.
+Prints ONE JSON line.  `value` is algorithmic TFLOP/s of the step (attention + scoring FLOP over
+visible keys only, divided by the step time); `roofline` describes the dominant kernel (the
+attention call) from HIP-event timings taken inside the timed region; `cpu_baseline` is the fp64
+oracle timed on this machine's host cores on a bounded row sample.  The line is only printed with a
+zero exit status when the sampled outputs are within the parity bar of the oracle.
+
+`--workload config3` runs the 30-layer stack instead (per layer: score, classify with N = 3, pack,
+attention, append; then one classification over all 360 heads); its JSON line carries per-layer
+times and the classification margins.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -29,11 +40,38 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, datasheet
+# What a kernel made of nothing but v_mfma_f32_32x32x16_bf16 sustains on this part (power-limited clock
+# of about 2.0 GHz instead of the 2.4 GHz of the datasheet figure); measured, see the design doc
+SUSTAINED_BF16_TFLOPS = 2100.0
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, datasheet
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3  # parity bar of the bf16 outputs against the fp64 oracle
 
-# HBM bytes per attention launch from rocprofv3 --pmc runs (FETCH_SIZE / WRITE_SIZE scaled by a
-# copy kernel of known size); see profiles/.  None = not measured for that workload yet.
-MEASURED_TRAFFIC_BYTES = {"config2_wan1.3b_480p": 268.7e6}   # profiles/config2_hot_path_rocprofv3.md
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+KERNEL_SOURCES = ["df_attn.hip", "df_attn_phase.inc", "df_cache.hip", "df_internal.h"]
+
+
+def kernel_source_hash() -> str:
+    """Identifies the kernel sources a profile was taken with (the GPU machine has no git history)."""
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2601_20499_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload_name: str):
+    """HBM bytes per attention call from the rocprofv3 --pmc runs summarised under profiles/
+    (FETCH_SIZE / WRITE_SIZE scaled by a copy of known size).  None when no profile of the current
+    kernel sources exists for the workload: a stale figure is never reported."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        return None
+    entry = table.get(workload_name)
+    if not entry or entry.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return entry.get("attn_call_bytes")
 
 
 def _blas_threads() -> int:
@@ -46,15 +84,28 @@ def _blas_threads() -> int:
         return os.cpu_count() or 1
 
 
+def oracle_rows(w, rows):
+    """The fp64 oracle on the same bf16-rounded inputs, on a subset of query rows (cpu_baseline leg)."""
+    import torch
+    from oracle import df_oracle as orc
+    b = lambda t: t.to(torch.bfloat16).double().numpy()
+    kh = [b(w.k_hist[:, h]) for h in range(w.H)]
+    vh = [b(w.v_hist[:, h]) for h in range(w.H)]
+    return orc.layer_attention(b(w.q), kh, vh, b(w.k_cur), b(w.v_cur), w.n_sink, w.n_win, w.scale, rows=rows)
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config4", "config5", "dhp3"],
-                    help="config2 is the headline workload; dhp3 = the paper's full method on the same geometry "
-                         "(sink / neighbour / packed dummy heads from Dynamic Head Programming, half of the heads dummy)")
+    ap.add_argument("--workload", default="config2",
+                    choices=["config1", "config2", "config3", "config4", "config5", "dhp3"],
+                    help="config2 is the headline workload; config3 = the 30-layer stack with per-layer head programming; "
+                         "dhp3 = the paper's full method on the config-2 geometry (sink / neighbour / packed dummy heads "
+                         "from Dynamic Head Programming, half of the heads dummy)")
     ap.add_argument("--layer", type=int, default=3, help="layer of the seeded 30-layer stack (dhp3 only)")
+    ap.add_argument("--layers", type=int, default=30, help="layers of the stack to run (config3 only)")
     ap.add_argument("--variants", action="store_true",
                     help="dhp3 only: also time df_attn_fwd under the ablation's other head typings (Tab. 6) and dense")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -114,46 +165,26 @@ def build_state(w, df, torch, dev):
     return st
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-    import torch
-    from paper_2601_20499_amd import binding as df
-    from paper_2601_20499_amd import workloads as wl
+def retype(w, df, types):
+    """The workload under other head types: contexts from df_head_context (Eq. 2 / 5 / 8)."""
+    import copy
+    v = copy.copy(w)
+    v.head_type, v.n_sink, v.n_win = list(types), [0] * w.H, [0] * w.H
+    for h, t in enumerate(types):
+        v.n_sink[h], v.n_win[h] = df.df_head_context(t, w.T, w.sink_frames, w.hist_frames - w.sink_frames)
+    return v
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = torch.device("cuda:0")
-    mode = df.DF_CLASSIFY_TWO_CLASS
-    if args.workload == "dhp3":
-        # head types are not given: they come out of the scores (Dynamic Head Programming, Eq. 6-7)
-        mode = df.DF_CLASSIFY_DHP
-        w = wl.dhp3_layer(args.layer)
-        kp, _, off0, sl0 = wl.packed_history(w)
-        F0 = torch.empty(w.H, 3, dtype=torch.float32, device=dev)
-        ws0 = torch.empty(df.df_attn_workspace_bytes(w.H, w.d, w.Nq), dtype=torch.uint8, device=dev)
-        df.df_head_score(w.q.to(dev), w.k_cur.to(dev), kp.to(dev), off0, sl0, F0, w.scale,
-                         q_sample_stride=4, q_offset=0, workspace=ws0)
-        base_types, _ = df.df_classify(F0.cpu().tolist(), w.H // 2, mode)
-        del kp, F0, ws0
 
-        def typed(types):
-            import copy
-            v = copy.copy(w)
-            v.head_type, v.n_sink, v.n_win = list(types), [0] * w.H, [0] * w.H
-            for h, t in enumerate(types):
-                v.n_sink[h], v.n_win[h] = df.df_head_context(t, w.T, w.sink_frames, w.hist_frames - w.sink_frames)
-            return v
-        packed = [df.DF_HEAD_PACK_DUMMY if t == df.DF_HEAD_DUMMY else t for t in base_types]
-        w = typed(packed)                      # dummy heads keep one packing frame (Eq. 8)
-    else:
-        w = getattr(wl, args.workload)()
-    st = build_state(w, df, torch, dev)
+def stats(xs):
+    return {"mean": round(statistics.fmean(xs), 4), "median": round(statistics.median(xs), 4), "min": round(min(xs), 4)}
+
+
+def timed_steps(w, st, df, torch, K, W, mode, calib_copy_mb=0):
+    """W untimed + K timed steps.  Returns the wall time of the K steps in ms per step (GPU work synchronised,
+    host classification included), per-call HIP-event times per step, and the head types of the last step."""
     H = w.H
-    n_dummy = sum(1 for t in w.head_type if t in (wl.HEAD_DUMMY, wl.HEAD_PACK_DUMMY))
-    K, W = args.steps, args.warmup
+    dev = st["q"].device
+    n_dummy = sum(1 for t in w.head_type if t in (df.DF_HEAD_DUMMY, df.DF_HEAD_PACK_DUMMY))
     F_host = [torch.empty(H, 3, dtype=torch.float32).pin_memory() for _ in range(K + W)]
     ev = lambda: torch.cuda.Event(enable_timing=True)
     names = ["score", "pack", "attn", "append"]
@@ -179,8 +210,8 @@ def main():
         df.df_kv_append(cb, st["k_cur"], st["v_cur"])
         m[4].record()
 
-    if args.calib_copy_mb:
-        src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
+    if calib_copy_mb:
+        src = torch.empty(calib_copy_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
         dst.copy_(src)                      # reads and writes calib_copy_mb MiB each
         torch.cuda.synchronize()
@@ -192,14 +223,122 @@ def main():
     for i in range(W, W + K):
         one_step(i)
     torch.cuda.synchronize()
-    types = None
+    types, keys = None, None
     for i in range(W, W + K):          # host part of the step: classification of the copied scores
-        types, _ = df.df_classify(F_host[i].tolist(), n_dummy, mode)
+        types, keys = df.df_classify(F_host[i].tolist(), n_dummy, mode)
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / K
+    per = {n: [marks[i][j].elapsed_time(marks[i][j + 1]) for i in range(W, W + K)] for j, n in enumerate(names)}
+    per["gpu_step"] = [marks[i][0].elapsed_time(marks[i][4]) for i in range(W, W + K)]
+    return ms_step, per, types, keys, F_host[W + K - 1].clone(), snap
 
-    per = {n: sum(marks[i][j].elapsed_time(marks[i][j + 1]) for i in range(W, W + K)) / K
-           for j, n in enumerate(names)}
+
+def run_config3(args, df, wl, torch, dev):
+    """The 30-layer stack: per layer the whole path with the head types coming out of df_head_score ->
+    df_classify (2 classes, N = 3), then one classification over all 360 heads (N = 90)."""
+    K, W = max(1, min(args.steps, 5)), max(1, min(args.warmup, 2))
+    layers, F_all = [], []
+    t_total = {"score": 0.0, "pack": 0.0, "attn": 0.0, "append": 0.0}
+    flop_total, ms_total = 0.0, 0.0
+    for layer in range(args.layers):
+        w0 = wl.config3_layer(layer)
+        # head types are not given: a first scoring call yields them, as in the step that is timed afterwards
+        kp, _, off0, sl0 = wl.packed_history(w0)
+        F0 = torch.empty(w0.H, 3, dtype=torch.float32, device=dev)
+        ws0 = torch.empty(df.df_attn_workspace_bytes(w0.H, w0.d, w0.Nq), dtype=torch.uint8, device=dev)
+        df.df_head_score(w0.q.to(dev), w0.k_cur.to(dev), kp.to(dev), off0, sl0, F0, w0.scale,
+                         q_sample_stride=4, q_offset=0, workspace=ws0)
+        F_layer = F0.cpu()
+        types0, keys0 = df.df_classify(F_layer.tolist(), 3, df.DF_CLASSIFY_TWO_CLASS)
+        del kp, F0, ws0
+        w = retype(w0, df, types0)
+        st = build_state(w, df, torch, dev)
+        ms_step, per, types, keys, F_last, _ = timed_steps(w, st, df, torch, K, W, df.DF_CLASSIFY_TWO_CLASS)
+        assert list(types) == list(types0), (layer, types, types0)
+        dummies = [h for h, t in enumerate(types) if t == df.DF_HEAD_DUMMY]
+        srt = sorted(keys)
+        layers.append({"layer": layer, "planted": list(w0.planted), "dummy": dummies,
+                       "margin": round(srt[3] - srt[2], 5),
+                       "attn_ms": round(statistics.median(per["attn"]), 4),
+                       "score_ms": round(statistics.median(per["score"]), 4),
+                       "attn_TFLOPs": round(w.attn_flop() / statistics.median(per["attn"]) / 1e9, 1)})
+        for k in t_total:
+            t_total[k] += statistics.median(per[k])
+        flop_total += w.attn_flop() + w.score_flop(4)
+        ms_total += ms_step
+        F_all += F_layer.tolist()
+        print(f"# layer {layer}: planted {w0.planted} -> dummy {dummies}, attention {layers[-1]['attn_ms']} ms "
+              f"({layers[-1]['attn_TFLOPs']} TFLOP/s), margin {layers[-1]['margin']}", file=sys.stderr, flush=True)
+        del st, w, w0
+        torch.cuda.empty_cache()
+    g_types, g_keys = df.df_classify(F_all, 3 * args.layers, df.DF_CLASSIFY_TWO_CLASS)
+    g_sorted = sorted(g_keys)
+    n_g = 3 * args.layers
+    per_layer_dummy = [sum(1 for t in g_types[12 * i:12 * i + 12] if t == df.DF_HEAD_DUMMY) for i in range(args.layers)]
+    attn_ms = [l["attn_ms"] for l in layers]
+    result = {
+        "metric": "head-heterogeneous attention TFLOP/s + ms per chunk-layer; % bf16 MFMA peak",
+        "value": round(flop_total / (ms_total * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_total / args.layers, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config3_stack_{args.layers}_layers", "H": 12, "d": 128, "tokens_per_frame": 1560, "Nq": 4680,
+                   "history_frames": 21, "step": "per layer: head_score+classify(N=3), pack+attn(fused score)+append"},
+        "stack_ms": {k: round(v, 3) for k, v in t_total.items()},
+        "attn_ms_per_layer": stats(attn_ms),
+        "roofline": {"bound": "mfma", "kernel": "df_attn_fwd (df_attn_kernel + df_attn_merge_kernel), median over layers",
+                     "achieved": round(statistics.median(l["attn_TFLOPs"] for l in layers), 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(statistics.median(l["attn_TFLOPs"] for l in layers) / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None},
+        "classification": {"per_layer_N": 3, "min_margin": min(l["margin"] for l in layers),
+                           "layers_where_dummy_is_subset_or_superset_of_planted": sum(
+                               1 for l in layers if set(l["dummy"]) <= set(l["planted"]) or set(l["planted"]) <= set(l["dummy"])),
+                           "global_n": 12 * args.layers, "global_N": n_g,
+                           "global_margin": round(g_sorted[n_g] - g_sorted[n_g - 1], 5) if n_g < len(g_sorted) else None,
+                           "global_dummy_per_layer": per_layer_dummy},
+        "layers": layers,
+    }
+    print(json.dumps(result), flush=True)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2601_20499_amd import binding as df
+    from paper_2601_20499_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    if args.workload == "config3":
+        run_config3(args, df, wl, torch, dev)
+        return
+    mode = df.DF_CLASSIFY_TWO_CLASS
+    if args.workload == "dhp3":
+        # head types are not given: they come out of the scores (Dynamic Head Programming, Eq. 6-7)
+        mode = df.DF_CLASSIFY_DHP
+        w = wl.dhp3_layer(args.layer)
+        kp, _, off0, sl0 = wl.packed_history(w)
+        F0 = torch.empty(w.H, 3, dtype=torch.float32, device=dev)
+        ws0 = torch.empty(df.df_attn_workspace_bytes(w.H, w.d, w.Nq), dtype=torch.uint8, device=dev)
+        df.df_head_score(w.q.to(dev), w.k_cur.to(dev), kp.to(dev), off0, sl0, F0, w.scale,
+                         q_sample_stride=4, q_offset=0, workspace=ws0)
+        base_types, _ = df.df_classify(F0.cpu().tolist(), w.H // 2, mode)
+        del kp, F0, ws0
+        packed = [df.DF_HEAD_PACK_DUMMY if t == df.DF_HEAD_DUMMY else t for t in base_types]
+        w_base = w
+        w = retype(w, df, packed)              # dummy heads keep one packing frame (Eq. 8)
+    else:
+        w = getattr(wl, args.workload)()
+    st = build_state(w, df, torch, dev)
+    H = w.H
+    n_dummy = sum(1 for t in w.head_type if t in (wl.HEAD_DUMMY, wl.HEAD_PACK_DUMMY))
+    K, W = args.steps, args.warmup
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    ms_step, per, types, _, _, snap = timed_steps(w, st, df, torch, K, W, mode, args.calib_copy_mb)
+
     attn_flop = w.attn_flop()
     score_flop = w.score_flop(4)
     designated = [h for h, t in enumerate(w.head_type) if t in (wl.HEAD_DUMMY, wl.HEAD_PACK_DUMMY)]
@@ -207,11 +346,13 @@ def main():
     if args.workload == "dhp3":
         assert list(types) == list(base_types), (types, base_types)
     value = (attn_flop + score_flop) / (ms_step * 1e-3) / 1e12
-    attn_tflops = attn_flop / (per["attn"] * 1e-3) / 1e12
+    attn_ms = statistics.fmean(per["attn"])
+    attn_tflops = attn_flop / (attn_ms * 1e-3) / 1e12
     pack_bytes = 2 * 2 * sum(w.visible_len(h) for h in range(H)) * w.d * 2
-    kept = sum(1 for h in range(H) if st["sink_cap"][h] + st["win_cap"][h] > 0)
     app_tokens = sum(min(w.Nc, st["win_cap"][h]) for h in range(H))
     append_bytes = 2 * 2 * app_tokens * w.d * 2
+    pack_ms, append_ms = statistics.fmean(per["pack"]), statistics.fmean(per["append"])
+    plan = df.df_attn_plan(w.Nq, w.Nc, [w.visible_len(h) for h in range(H)], [min(w.n_sink[h], w.Nh) for h in range(H)])
 
     result = {
         "metric": "head-heterogeneous attention TFLOP/s + ms per chunk-layer; % bf16 MFMA peak",
@@ -221,16 +362,23 @@ def main():
         "config": {"workload": w.name, "H": H, "d": w.d, "tokens_per_frame": w.T, "Nq": w.Nq,
                    "keys_per_head": [w.visible_len(h) + w.Nc for h in range(H)],
                    "dummy_heads": n_dummy, "step": "head_score+classify, pack+attn(fused score)+append",
+                   "value_is": "(attention + head_score algorithmic FLOP) / step time",
                    "classified_dummy": [h for h, t in enumerate(types) if t == df.DF_HEAD_DUMMY]},
-        "roofline": {"bound": "mfma", "kernel": "df_attn_fwd = df_attn_kernel + df_attn_merge_kernel + df_score_finish_kernel", "achieved": round(attn_tflops, 2),
+        "roofline": {"bound": "mfma", "kernel": "df_attn_fwd = df_attn_kernel + df_attn_merge_kernel",
+                     "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "flop_per_launch": attn_flop,
-                     "ms_per_launch": round(per["attn"], 4)},
-        "breakdown_ms": {k: round(v, 4) for k, v in per.items()},
-        "attn_ms_per_chunk_layer": round(per["attn"], 4),
-        "pack_GBps": round(pack_bytes / (per["pack"] * 1e-3) / 1e9, 1) if pack_bytes else None,
-        "append_GBps": round(append_bytes / (per["append"] * 1e-3) / 1e9, 1) if append_bytes else None,
-        "pack_frac_hbm": round(pack_bytes / (per["pack"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if pack_bytes else None,
+                     "traffic": measured_traffic(w.name), "flop_per_launch": attn_flop,
+                     "ms_per_launch": round(attn_ms, 4), "ms_per_launch_median": round(statistics.median(per["attn"]), 4),
+                     "ms_per_launch_min": round(min(per["attn"]), 4),
+                     "peak_sustained": SUSTAINED_BF16_TFLOPS, "frac_of_sustained": round(attn_tflops / SUSTAINED_BF16_TFLOPS, 4),
+                     "kernel_source_hash": kernel_source_hash()},
+        "attention_TFLOPs": round(attn_tflops, 2),
+        "breakdown_ms": {k: stats(v) for k, v in per.items()},
+        "attn_ms_per_chunk_layer": round(attn_ms, 4),
+        "attn_plan": {k: plan[k] for k in ("n_qtiles", "team_size", "n_groups", "n_teams", "workgroups", "cut_units", "busy")},
+        "pack_GBps": round(pack_bytes / (pack_ms * 1e-3) / 1e9, 1) if pack_bytes else None,
+        "append_GBps": round(append_bytes / (append_ms * 1e-3) / 1e9, 1) if append_bytes else None,
+        "pack_frac_hbm": round(pack_bytes / (pack_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if pack_bytes else None,
         "paper_context": "H100 end-to-end only: up to 2.0x speedup, 24.3 FPS, 17.6->19.6 FPS from pruning 25% of heads",
     }
 
@@ -262,19 +410,26 @@ def main():
             c2 = df.Cache(kc, vc, list(st["cache"].head_row_off), st["sink_cap"], st["win_cap"], w.d)
             sets.append((c2, torch.empty(n_rows, w.d, dtype=torch.bfloat16, device=dev),
                          torch.empty(n_rows, w.d, dtype=torch.bfloat16, device=dev)))
+        # plain-copy ceiling: ONE launch that reads and writes the pack's bytes contiguously, same rotation
+        flat = [(torch.empty(2 * n_rows, w.d, dtype=torch.bfloat16, device=dev).fill_(1.0),
+                 torch.empty(2 * n_rows, w.d, dtype=torch.bfloat16, device=dev)) for _ in range(n_sets)]
         reps = 120
 
         def timed(fn):
             for i in range(len(sets)):
                 fn(i)
             torch.cuda.synchronize()
-            e0, e1 = ev(), ev()
-            e0.record()
-            for i in range(reps):
-                fn(i % len(sets))
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) * 1e3 / reps
+            best = None
+            for _ in range(3):
+                e0, e1 = ev(), ev()
+                e0.record()
+                for i in range(reps):
+                    fn(i % len(sets))
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / reps
+                best = us if best is None else min(best, us)
+            return best
 
         for c2, _, _ in sets:
             for h in range(H):
@@ -291,21 +446,21 @@ def main():
         def do_append(i):          # these private caches simply keep rolling: every call moves the same bytes
             appends[i]()
 
-        def do_plain(i):           # a plain device copy of the same bytes, same rotation: the box's ceiling
-            c2, ko, vo = sets[i]
-            ko.copy_(c2.k_cache[:n_rows])
-            vo.copy_(c2.v_cache[:n_rows])
+        def do_plain(i):           # a plain contiguous device copy of the pack's bytes in one launch: the box's ceiling
+            flat[i][1].copy_(flat[i][0])
 
         pack_us, app_us, plain_us = timed(do_pack), timed(do_append), timed(do_plain)
         result["copies"] = {
-            "method": f"{reps} launches back to back over {len(sets)} buffer sets ({len(sets) * pack_bytes / 1e6:.0f} MB in rotation)",
+            "method": f"best of 3 x {reps} launches back to back over {len(sets)} buffer sets ({len(sets) * pack_bytes / 1e6:.0f} MB in rotation)",
             "plain_copy_same_bytes": {"us": round(plain_us, 2), "GBps": round(pack_bytes / plain_us / 1e3, 1),
-                                      "note": "two torch copy_ launches (K and V)"},
+                                      "frac_hbm": round(pack_bytes / plain_us / 1e3 / PEAK_HBM_GBS, 4),
+                                      "note": "one contiguous torch copy_ of the pack's bytes: what a copy of this size reaches on this box"},
             "pack": {"us": round(pack_us, 2), "bytes": pack_bytes, "GBps": round(pack_bytes / pack_us / 1e3, 1),
-                     "frac_hbm": round(pack_bytes / pack_us / 1e3 / PEAK_HBM_GBS, 4)},
+                     "frac_hbm": round(pack_bytes / pack_us / 1e3 / PEAK_HBM_GBS, 4),
+                     "frac_of_plain_copy": round(plain_us / pack_us, 3)},
             "append": {"us": round(app_us, 2), "bytes": append_bytes, "GBps": round(append_bytes / app_us / 1e3, 1),
                        "frac_hbm": round(append_bytes / app_us / 1e3 / PEAK_HBM_GBS, 4)} if append_bytes else None}
-        del sets
+        del sets, flat
 
     if args.workload == "dhp3":
         result["config"]["head_types"] = list(w.head_type)
@@ -323,7 +478,7 @@ def main():
         }
         res = {}
         for name, tys in variants.items():
-            v = typed(tys)
+            v = retype(w_base, df, tys)
             kp, vp, off, sl = wl.packed_history(v)
             kp, vp = kp.to(dev), vp.to(dev)
             for _ in range(3):
@@ -344,19 +499,25 @@ def main():
             r["speedup_vs_dense"] = round(dense / r["attn_ms"], 3)
         result["variants"] = res
 
+    ok = True
     if not args.no_cpu_baseline:
         import numpy as np
-        from tests import gpu_util as gu  # row sampler and the oracle driver shared with the parity tests
+        # the last timed call wrote st["out"] through the in-place path: run the packed path once more so that the
+        # outputs compared with the oracle are those of the step's own df_attn_fwd call
+        off, sl = df.df_pack_context(st["cache"], st["sink_cap"], st["win_cap"], st["k_pack"], st["v_pack"])
+        df.df_attn_fwd(st["q"], st["k_cur"], st["v_cur"], st["k_pack"], st["v_pack"], off, sl, st["out"],
+                       w.scale, score_out=st["F_fused"], workspace=st["ws"])
+        torch.cuda.synchronize()
         n_rows = args.cpu_rows
         if n_rows <= 0:
-            gu.oracle_rows(w, rows=np.arange(8))                       # warm the BLAS threads
+            oracle_rows(w, np.arange(8))                               # warm the BLAS threads
             t = time.perf_counter()
-            gu.oracle_rows(w, rows=np.arange(0, w.Nq, max(1, w.Nq // 64))[:64])
+            oracle_rows(w, np.arange(0, w.Nq, max(1, w.Nq // 64))[:64])
             rate = 64 / max(time.perf_counter() - t, 1e-3)
             n_rows = int(max(32, min(w.Nq, rate * 15)))
         rows = np.linspace(0, w.Nq - 1, n_rows).astype(np.int64)
         t = time.perf_counter()
-        ref, _, _ = gu.oracle_rows(w, rows=rows)
+        ref, _, _ = oracle_rows(w, rows)
         dt = time.perf_counter() - t
         got = st["out"].float().cpu().double().numpy()[rows]
         err = np.abs(got - ref)
@@ -366,8 +527,13 @@ def main():
                                   "sample": f"{len(rows)} of {w.Nq} query rows of every head, all visible keys, "
                                             f"fp64 numpy, {dt:.1f} s",
                                   "ms_per_chunk_layer_extrapolated": round(dt * 1e3 * w.Nq / len(rows), 1)}
-        result["parity_on_sample"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean())}
+        ok = bool(np.isfinite(got).all() and err.max() <= MAX_ABS and err.mean() <= MEAN_ABS)
+        result["parity_on_sample"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean()),
+                                      "bar": {"max_abs": MAX_ABS, "mean_abs": MEAN_ABS}, "ok": ok}
     print(json.dumps(result), flush=True)
+    if not ok:
+        print("bench.py: sampled outputs are outside the parity bar of the oracle", file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -198,20 +198,23 @@ __host__ __device__ __forceinline__ int head_of_column(const AttnParams &p, int 
   return hh;
 }
 
-// Normalise, round and store one thread's share of a finished unit; returns nothing.
+// Normalise, round and store one thread's share of 32 output columns (block db) of a finished unit.
+__device__ __forceinline__ void store_output_block(const AttnParams &p, int h, int row, int hf, int db, const f32x16 &o,
+                                                   float inv) {
+  u16 *dst = p.out + row * p.o_st + h * p.o_sh + 4 * hf + 32 * db;
+#pragma unroll
+  for (int cq = 0; cq < 4; ++cq) {
+    uint2 w;
+    w.x = pack_bf16x2(o[4 * cq] * inv, o[4 * cq + 1] * inv);
+    w.y = pack_bf16x2(o[4 * cq + 2] * inv, o[4 * cq + 3] * inv);
+    *reinterpret_cast<uint2 *>(dst + 8 * cq) = w;
+  }
+}
 template <int D>
 __device__ __forceinline__ void store_output(const AttnParams &p, int h, int row, int hf, const f32x16 (&o)[D / 32],
                                              float inv) {
-  u16 *dst = p.out + row * p.o_st + h * p.o_sh + 4 * hf;
 #pragma unroll
-  for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-    for (int cq = 0; cq < 4; ++cq) {
-      uint2 w;
-      w.x = pack_bf16x2(o[db][4 * cq] * inv, o[db][4 * cq + 1] * inv);
-      w.y = pack_bf16x2(o[db][4 * cq + 2] * inv, o[db][4 * cq + 3] * inv);
-      *reinterpret_cast<uint2 *>(dst + 32 * db + 8 * cq) = w;
-    }
+  for (int db = 0; db < D / 32; ++db) store_output_block(p, h, row, hf, db, o[db], inv);
 }
 
 // Sum of the two region masses over the 256 rows of a unit, in a fixed order (deterministic): a
@@ -604,24 +607,25 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   }
 }
 
-// Second kernel.  Workgroup (k, member) looks at the boundary between spans k-1 and k: if it falls inside
-// a head (not on its first column), the unit (group, head, member's query tile) was cut there and is
-// put together from the partial results of its pieces, in key order, with the usual log-sum-exp
-// weights; a unit cut by several boundaries is handled at the first of them.  When scores are wanted,
-// the workgroup that completes the last unit of a head (counted per head) sums the head's per-tile
-// masses in tile order; heads that were not cut anywhere get a workgroup of their own for that
-// (index >= (n_teams - 1) * team_size).
+// Second kernel.  Workgroup (k, member; db) looks at the boundary between spans k-1 and k: if it falls
+// inside a head (not on its first column), the unit (group, head, member's query tile) was cut there
+// and is put together from the partial results of its pieces, in key order, with the usual
+// log-sum-exp weights; a unit cut by several boundaries is handled at the first of them.  blockIdx.y
+// = db selects 32 of the D output columns, so that a unit is spread over D/32 workgroups (the kernel
+// is a pure data mover and wants many loads in flight).  When scores are wanted, the db = 0 workgroup
+// that completes the last unit of a head (counted per head) sums the head's per-tile masses in tile
+// order; heads that were not cut anywhere get a workgroup of their own for that
+// (blockIdx.x >= (n_teams - 1) * team_size).
 template <int D, bool SCORE_ONLY>
 __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParams p) {
-  constexpr int DB = D / 32;
   __shared__ float lds_red[kWaves * 2];
-  __shared__ int lds_last;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63, j = lane & 31, hf = lane >> 5;
+  const int db = int(blockIdx.y);
   const int n_merge = (p.n_teams - 1) * p.team_size;
   if (int(blockIdx.x) >= n_merge) {                // score of a head no boundary cuts
     const int h = int(blockIdx.x) - n_merge;
-    if (tid == 0 && p.n_cut_units[h] == 0) finish_score(p, h);
+    if (db == 0 && tid == 0 && p.n_cut_units[h] == 0) finish_score(p, h);
     return;
   }
   const int k = int(blockIdx.x) / p.team_size + 1, member = int(blockIdx.x) % p.team_size;
@@ -640,11 +644,9 @@ __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParam
   while (span_begin(s_hi + 1, p.line_len, p.n_teams) < u_hi) ++s_hi;
 
   float M = -INFINITY, Lt = 0.f, La = 0.f, Lb = 0.f;
-  f32x16 o[DB];
+  f32x16 o;
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+  for (int v = 0; v < 16; ++v) o[v] = 0.f;
 #pragma unroll 1
   for (int sp = s_lo; sp <= s_hi; ++sp) {
     const int64_t b = span_begin(sp, p.line_len, p.n_teams);
@@ -660,32 +662,29 @@ __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParam
     Lb = Lb * w_old + st.w * w_new;
     if (!SCORE_ONLY) {
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int cq = 0; cq < 4; ++cq) {
-          const float4 v4 = *reinterpret_cast<const float4 *>(Slot<D>::ovec(const_cast<float *>(slot), tid, db * 4 + cq));
-          o[db][4 * cq] = o[db][4 * cq] * w_old + v4.x * w_new;
-          o[db][4 * cq + 1] = o[db][4 * cq + 1] * w_old + v4.y * w_new;
-          o[db][4 * cq + 2] = o[db][4 * cq + 2] * w_old + v4.z * w_new;
-          o[db][4 * cq + 3] = o[db][4 * cq + 3] * w_old + v4.w * w_new;
-        }
+      for (int cq = 0; cq < 4; ++cq) {
+        const float4 v4 = *reinterpret_cast<const float4 *>(Slot<D>::ovec(const_cast<float *>(slot), tid, db * 4 + cq));
+        o[4 * cq] = o[4 * cq] * w_old + v4.x * w_new;
+        o[4 * cq + 1] = o[4 * cq + 1] * w_old + v4.y * w_new;
+        o[4 * cq + 2] = o[4 * cq + 2] * w_old + v4.z * w_new;
+        o[4 * cq + 3] = o[4 * cq + 3] * w_old + v4.w * w_new;
+      }
     }
   }
   const float inv = 1.f / Lt;
   const int row = qt * kBQ + wave * 32 + j;
   const bool valid = row < p.Nq;
   if (!SCORE_ONLY && valid) {
-    store_output<D>(p, h, row, hf, o, inv);
-    if (p.lse != nullptr && hf == 0) p.lse[int64_t(h) * p.Nq + row] = M * p.scale + __logf(Lt);
+    store_output_block(p, h, row, hf, db, o, inv);
+    if (db == 0 && p.lse != nullptr && hf == 0) p.lse[int64_t(h) * p.Nq + row] = M * p.scale + __logf(Lt);
   }
-  if (p.part != nullptr) {
+  if (db == 0 && p.part != nullptr) {
     reduce_masses(p, lds_red, h, qt, tid, valid ? La * inv : 0.f, valid ? Lb * inv : 0.f);
     // the unit's masses are out; whoever completes the head's last merged unit sums the head
     if (tid == 0) {
       __threadfence();
       const int done = __hip_atomic_fetch_add(p.tickets + h, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      lds_last = (done == p.n_cut_units[h] - 1);
-      if (lds_last) {
+      if (done == p.n_cut_units[h] - 1) {
         __threadfence();
         finish_score(p, h);
       }
@@ -783,7 +782,8 @@ static df_status launch(AttnParams &p, void *workspace, float *score_out, hipStr
   // second launch: units cut by span boundaries, and the per-head score sums
   const int n_merge = (p.n_teams - 1) * p.team_size + (score_out ? p.H : 0);
   if (n_merge > 0) {
-    hipLaunchKernelGGL((df_attn_merge_kernel<D, SCORE_ONLY>), dim3(n_merge), dim3(kThreads), 0, st, p);
+    hipLaunchKernelGGL((df_attn_merge_kernel<D, SCORE_ONLY>), dim3(n_merge, SCORE_ONLY ? 1 : D / 32), dim3(kThreads), 0, st,
+                       p);
     if (df_status s = launch_status()) return s;
   }
   return DF_OK;
