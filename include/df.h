@@ -85,6 +85,26 @@ df_status df_head_context(int32_t head_type, int32_t T, int32_t sink_frames,
  * Optionally also returns, per head, the frame attention score of Eq. 3 under
  * the head's own visibility: the mean over all Nq queries of the attention
  * mass on (sink region, neighbour region, current chunk).
+ *
+ * Launches: one kernel, plus a small second one when score_out is given.  The
+ * keys of a (head, query tile) unit may be split between workgroups; when the
+ * device has a compute unit for every workgroup of the launch (it has on the
+ * part this library is written for) the partial sums travel from workgroup to
+ * workgroup through the workspace while the kernel runs, each waiting for the
+ * one before it with a bounded wait: should a workgroup never get to run
+ * (compute units taken away from the process), the rows concerned come out as
+ * NaN after some seconds instead of hanging the device.  DF_ATTN_HANDOVER=0 in
+ * the environment (read at every call) selects the other path, in which a
+ * second kernel puts those units together; the results are the same bit for bit.
+ * Two calls that use the same workspace must not overlap on the device.
+ *
+ * Under HIP graph capture: the call records kernels only (no memset, no copy),
+ * but everything the host passes by value is frozen into them - shapes,
+ * strides, pointers and the per-head tables hist_off / hist_sink_len /
+ * hist_len.  A captured graph therefore stays valid only while the cache state
+ * it was captured in holds (same head types, same per-head lengths, same
+ * buffers); the data in the buffers may change.  After df_cache_append has
+ * changed a length, or df_cache_pack has re-typed the heads, capture again.
  * ---------------------------------------------------------------------- */
 typedef struct df_attn_args {
   const void *q;            /* DEVICE bf16, element (u,h,c) at q[u*q_stride_tok + h*q_stride_head + c] */
@@ -126,7 +146,7 @@ df_status df_attn_fwd(const df_attn_args *args, void *stream);
  * inside the library, which every GPU the library runs on holds until the process ends.  Same
  * kernels, same results bit for bit, same validation and error codes as df_attn_fwd, plus
  * DF_ERR_WORKSPACE when df_attn_workspace_bytes(H, d, Nq) exceeds DF_STATIC_SCRATCH_BYTES (with d = 128
- * that is H * ceil(Nq / 128) > 262128, i.e. more than 524160 queries at H = 64) and DF_ERR_LAUNCH when
+ * that is H * ceil(Nq / 128) > 130928, i.e. more than 261760 queries at H = 64) and DF_ERR_LAUNCH when
  * the runtime cannot give the array's address.  The call allocates nothing.  All calls on one GPU share the array: calls that
  * may overlap on one GPU (different streams, different threads) race and must be ordered by the
  * caller; nothing in it has to be cleared between calls. */

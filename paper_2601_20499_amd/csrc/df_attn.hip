@@ -7,15 +7,24 @@
 // chunk only: no masked tile is ever issued.  Heads differ in length by the ratio
 // of their contexts (3x between full and dummy heads, 20x with packed long
 // contexts), so heads are not dealt out whole.  The key tiles of all heads,
-// longest head first, form one line of "columns"; the line is cut into equal
-// spans, one per TEAM of workgroups.  A team has one workgroup per query tile:
-// its members walk the same columns at the same time, each for its own 256
-// queries, so they share every K/V tile in L2 while it is hot, and every team
-// does the same amount of work.  A head that lies inside one span is finished
-// in place; a head cut by a span boundary leaves per-piece partial results
-// (m, l, region sums, unnormalised O in fp32) in the workspace and a second
-// kernel merges them in key order.  Teams are laid out XCD-major (workgroup id
-// mod 8 selects the XCD), so a team sits on one or two XCDs.
+// longest head first, are the "columns"; query tiles are taken in groups of
+// team_size, and the line of (group, column) positions is cut into equal spans,
+// one per TEAM of workgroups.  A team has one workgroup per query tile of a
+// group: its members walk the same columns at the same time, each for its own
+// 256 queries, so they share every K/V tile in L2 while it is hot, and every
+// team does the same amount of work.  A unit that lies inside one span is
+// finished in place.  A unit cut by span boundaries is summed piece by piece
+// along the chain of workgroups that hold its pieces (same member of
+// consecutive teams): every workgroup walks its span from the END, so the piece
+// that begins a cut unit is the first thing a workgroup does and the piece that
+// completes one is the last, and each link finds the sum of the earlier pieces
+// (m, l, region sums, unnormalised O in fp32) waiting in the workspace, adds its
+// own in key order and either passes the sum on or writes the result.  This
+// needs every workgroup of the launch on the device at once; when the device
+// cannot hold them all, the pieces are left in the workspace and a second kernel
+// puts them together in the same order with the same arithmetic.  Teams are laid
+// out XCD-major (workgroup id mod 8 selects the XCD), so a team sits on one or
+// two XCDs.
 //
 // MFMA mapping.  Scores are computed transposed, S^T = K Q^T, with
 // v_mfma_f32_32x32x16_bf16: the K tile is the A operand (ds_read_b128 from a
@@ -48,12 +57,15 @@
 // is still "lane base + compile-time offset".  Tiles rotate through four LDS
 // buffers each; loads are issued two to three iterations before their first use.
 //
-// Online softmax keeps a running row maximum m and per-lane partial row sums
-// l in fp32.  The maximum is only raised (and O, l rescaled) when some row of
-// the wave exceeds it by more than 2^8, which keeps P within bf16/fp32 range
-// and makes rescaling rare; P is rounded to bf16 (RNE) before the second
-// product; l sums the unrounded fp32 values.  The output is divided by l and
-// rounded to bf16 once at the end.
+// Online softmax keeps a reference exponent m per row and per-lane partial row
+// sums l in fp32.  m is the maximum of the row's first tile and is NOT raised
+// tile by tile: exp2 of a logit above m simply exceeds one, which fp32 holds
+// with room to spare.  Only when a row's sum passes 2^100 (or is no longer
+// finite) is m raised to the row's current maximum plus the logarithm of the
+// sum and O, l rescaled, so the per-tile work has no row maximum, no
+// comparison against the old one and no rescaling; P is rounded to bf16 (RNE)
+// before the second product; l sums the unrounded fp32 values.  The output is
+// divided by l and rounded to bf16 once at the end.
 //
 // The frame attention score of Eq. 3 falls out of the same statistics: with the
 // keys ordered sink | window | current, snapshots (m1,l1) after the sink region
@@ -61,6 +73,8 @@
 // l1*2^(m1-m3)/l3, (l2*2^(m2-m3) - l1*2^(m1-m3))/l3 and the remainder.
 #include <algorithm>
 #include <cmath>
+#include <atomic>
+#include <cstdlib>
 #include <mutex>
 #include <numeric>
 #include <type_traits>
@@ -74,6 +88,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16;
 
@@ -86,6 +101,7 @@ constexpr float kSumLimit = 0x1p100f; // the reference of the exponentials is ra
 constexpr int kXcd = 8;            // XCDs per device: consecutive workgroup ids go to consecutive XCDs
 constexpr int kNumCU = 256;        // MI355X: one workgroup per CU (LDS-bound occupancy)
 constexpr int kMinSpan = 8;        // do not cut the work finer than this many key tiles per team
+constexpr int kSpinLimit = 1 << 22; // polls of a hand-over flag before a workgroup gives up (seconds; normally one poll)
 
 struct AttnParams {
   const u16 *q, *k_cur, *v_cur, *k_hist, *v_hist;
@@ -93,6 +109,9 @@ struct AttnParams {
   float *lse;          // [H, Nq] or null
   float *part;         // workspace: [H, n_qtiles, 4] partial score sums, or null
   int32_t *tickets;    // workspace: [H] counters of the merged units of a head (zeroed by the main kernel)
+  unsigned long long *flags;   // workspace: one word per workgroup, = epoch once its hand-over sum is in memory
+  unsigned long long epoch;    // this launch's flag value: random, so that memory never holds it by chance
+  int32_t handoff;     // cut units are put together inside the main kernel (needs all workgroups on the device at once)
   float *slots;        // workspace: 2 partial-result slots per workgroup (see Slot)
   float *score;        // [H, 3] frame attention scores, or null
   int64_t q_st, q_sh, kc_st, kc_sh, o_st, o_sh;
@@ -180,6 +199,41 @@ struct Slot {
   __device__ static float *ovec(float *slot, int tid, int i) { return slot + kStats + (i * kThreads + tid) * 4; }
 };
 
+// A partial result may be handed from one workgroup to another while the kernel runs (see the piece
+// loop).  The L2 caches of the eight XCDs are not kept coherent with each other for ordinary accesses,
+// so this data is written and read with the cache-control bits of a system-scope atomic access (sc0
+// sc1: stores write through to memory, loads are served from memory) - the same bits the compiler puts
+// on a relaxed system-scope atomic, here on 16-byte accesses - instead of cache maintenance, which
+// would also throw the K/V tiles the team shares out of L2.
+__device__ __forceinline__ void store4_through(float *ptr, float a, float b, float c, float d) {
+  const f32x4 v = {a, b, c, d};
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(ptr), "v"(v) : "memory");
+}
+// Four 16-byte loads at ptr + i * stride floats; returns when the data is in the registers.
+__device__ __forceinline__ void load4x4_through(const float *ptr, int stride, f32x4 (&v)[4]) {
+  const float *p1 = ptr + stride, *p2 = ptr + 2 * stride, *p3 = ptr + 3 * stride;
+  asm volatile(
+      "global_load_dwordx4 %0, %4, off sc0 sc1\n\t"
+      "global_load_dwordx4 %1, %5, off sc0 sc1\n\t"
+      "global_load_dwordx4 %2, %6, off sc0 sc1\n\t"
+      "global_load_dwordx4 %3, %7, off sc0 sc1\n\t"
+      "s_waitcnt vmcnt(0)"
+      : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+      : "v"(ptr), "v"(p1), "v"(p2), "v"(p3)
+      : "memory");
+}
+__device__ __forceinline__ f32x4 load4_through(const float *ptr) {
+  f32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1\n\ts_waitcnt vmcnt(0)" : "=&v"(v) : "v"(ptr) : "memory");
+  return v;
+}
+
+// Weighted sum of the earlier pieces' value and a later piece's, written out so that both places that
+// put pieces together (in the main kernel and in the merge kernel) round in the same way.
+__device__ __forceinline__ float fold(float earlier, float w_earlier, float later, float w_later) {
+  return __fmaf_rn(earlier, w_earlier, __fmul_rn(later, w_later));
+}
+
 // Partial-result slot of (span, first or later piece of the span, member of the team).
 __device__ __forceinline__ int64_t slot_index(const AttnParams &p, int span, int which, int member) {
   return int64_t(2 * span + which) * p.team_size + member;
@@ -264,6 +318,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds_k[kNBuf * L::KTILE];
   __shared__ __attribute__((aligned(16))) unsigned char lds_v[SCORE_ONLY ? 16 : kNBuf * L::VTILE];
   __shared__ float lds_red[kWaves * 2];
+  __shared__ int lds_ok;
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -298,11 +353,16 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
   const uint32_t lane_vo_hist = uint32_t(voff_hist) + uint32_t(wave) * L::ROWB;      // lane offset + this wave's first row group
   const uint32_t lane_vo_cur = uint32_t(voff_cur) + uint32_t(wave) * cur_stride_b;
 
+  // The pieces of the span are taken from its end to its start.  A head that a span boundary cuts in two
+  // is then begun by the workgroup that has it at the end of its span as the FIRST thing it does, and
+  // completed by the workgroup that has the rest at the start of its span as the LAST thing it does: by
+  // then the first part has long been in memory, and the second workgroup finishes the unit itself
+  // (hand-over) instead of leaving a partial result to a second kernel.
 #pragma unroll 1
-  for (int64_t pos = span_lo; pos < span_hi;) {
-    // ---- the piece at `pos`: group of query tiles, head, first and last tile of this team's share
-    const int grp = int(pos / p.total_cols);
-    const int col = int(pos - int64_t(grp) * p.total_cols);
+  for (int64_t pos_end = span_hi; pos_end > span_lo;) {
+    // ---- the piece that ends at `pos_end`: group of query tiles, head, first and last tile of this team's share
+    const int grp = int((pos_end - 1) / p.total_cols);
+    const int col = int((pos_end - 1) - int64_t(grp) * p.total_cols);
     const int hh = head_of_column(p, col);         // index into the length-sorted head order
     const int h = p.order[hh];
     const int64_t hoff = p.hist_off[h];
@@ -312,11 +372,16 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     const int nt1 = (len_h - sink + kKT - 1) / kKT;
     const int nt2 = (p.Nc + kKT - 1) / kKT;
     const int n_tiles = nt0 + nt1 + nt2;
-    const int t_begin = col - p.cum[hh];
-    const int t_end = int(min(int64_t(n_tiles), t_begin + (span_hi - pos)));
-    const bool whole = (t_begin == 0) && (t_end == n_tiles);
-    const int64_t piece_pos = pos;
-    pos += t_end - t_begin;
+    const int64_t unit_lo = int64_t(grp) * p.total_cols + p.cum[hh];   // line position of the unit's first tile
+    const int64_t piece_pos = max(span_lo, unit_lo);
+    const int t_begin = int(piece_pos - unit_lo);
+    const int t_end = int(pos_end - unit_lo);
+    pos_end = piece_pos;
+    // Hand-over: a piece that does not begin its unit takes over what the unit's earlier pieces have
+    // summed (always from the same member of the previous team: the pieces of a unit lie in consecutive
+    // spans), a piece that does not end its unit passes the sum on to the same member of the next team.
+    const bool take = p.handoff && t_begin > 0;
+    const bool give = p.handoff && t_end < n_tiles;
     const int qt = grp * p.team_size + member;     // this workgroup's query tile in this group
     if (qt >= p.n_qtiles) continue;                // the last group may have fewer tiles than the team has members
     const int q0 = qt * kBQ + wave * 32;
@@ -581,27 +646,77 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     const float l2 = pair_sum(snap_l1 * fast_exp2((snap_m1 - m) * p.c));   // sink + window regions
     const int row = q0 + j;
     const bool valid = row < p.Nq;
-    if (whole) {
-      const float inv = 1.f / lt;
+    float m_u = m, lt_u = lt, l1_u = l1, l2_u = l2;
+    if (take) {
+      // The earlier pieces' sum was written when the other workgroup began its span (or, if the unit covers
+      // that whole span, as soon as it had taken over from the one before it).  Wait until the flag says it
+      // is in memory; the wait is bounded so that a workgroup that never runs cannot hang the device: the
+      // rows then come out as NaN.
+      const int give_span = span - 1;
+      const bool give_at_start = unit_lo <= span_begin(give_span, p.line_len, p.n_teams);
+      const float *slot = p.slots + slot_index(p, give_span, give_at_start ? 0 : 1, member) * Slot<D>::kFloats;
+      if (tid == 0) {
+        unsigned long long *flag = p.flags + give_span * p.team_size + member;
+        int ok = 0;
+        for (int spin = 0; spin < kSpinLimit && !ok; ++spin) {
+          ok = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == p.epoch;
+          if (!ok) __builtin_amdgcn_s_sleep(16);
+        }
+        // the flag has one reader: put it back, so that a replay of this launch (same epoch) starts clean
+        __hip_atomic_store(flag, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        lds_ok = ok;
+      }
+      __syncthreads();
+      const float poison = lds_ok ? 0.f : NAN;
+      const f32x4 st = load4_through(Slot<D>::stats(const_cast<float *>(slot), tid));
+      // earlier pieces first: the same order and arithmetic as the merge kernel
+      const float m_new = fmaxf(st[0], m);
+      const float w_h = (st[0] == m_new) ? 1.f : fast_exp2((st[0] - m_new) * p.c);
+      const float w_t = (m == m_new) ? 1.f : fast_exp2((m - m_new) * p.c);
+      m_u = m_new + poison;
+      lt_u = fold(st[1], w_h, lt, w_t);
+      l1_u = fold(st[2], w_h, l1, w_t);
+      l2_u = fold(st[3], w_h, l2, w_t);
+      if (!SCORE_ONLY) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          f32x4 v[4];
+          load4x4_through(Slot<D>::ovec(const_cast<float *>(slot), tid, db * 4), kThreads * 4, v);
+#pragma unroll
+          for (int cq = 0; cq < 4; ++cq)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[db][4 * cq + e] = fold(v[cq][e], w_h, o[db][4 * cq + e], w_t);
+        }
+      }
+      __syncthreads();                             // lds_ok is free again
+    }
+    if (t_end == n_tiles && (t_begin == 0 || take)) {
+      // the unit is complete
+      const float inv = 1.f / lt_u;
       if (!SCORE_ONLY && valid) {
         store_output<D>(p, h, row, hf, o, inv);
-        if (p.lse != nullptr && hf == 0) p.lse[int64_t(h) * p.Nq + row] = m * p.scale + __logf(lt);
+        if (p.lse != nullptr && hf == 0) p.lse[int64_t(h) * p.Nq + row] = m_u * p.scale + __logf(lt_u);
       }
       if (p.part != nullptr)
-        reduce_masses(p, lds_red, h, qt, tid, valid ? l1 * inv : 0.f, valid ? l2 * inv : 0.f);
+        reduce_masses(p, lds_red, h, qt, tid, valid ? l1_u * inv : 0.f, valid ? l2_u * inv : 0.f);
     } else {
-      // a piece that starts at the span's first iteration uses the span's slot 0, a later one slot 1
+      // a piece that starts at the span's first position uses the span's slot 0, a later one slot 1
       float *slot = p.slots + slot_index(p, span, piece_pos == span_lo ? 0 : 1, member) * Slot<D>::kFloats;
-      float4 st = {m, lt, l1, l2};
-      *reinterpret_cast<float4 *>(Slot<D>::stats(slot, tid)) = st;
+      store4_through(Slot<D>::stats(slot, tid), m_u, lt_u, l1_u, l2_u);
       if (!SCORE_ONLY) {
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int cq = 0; cq < 4; ++cq) {
-            float4 v4 = {o[db][4 * cq], o[db][4 * cq + 1], o[db][4 * cq + 2], o[db][4 * cq + 3]};
-            *reinterpret_cast<float4 *>(Slot<D>::ovec(slot, tid, db * 4 + cq)) = v4;
-          }
+          for (int cq = 0; cq < 4; ++cq)
+            store4_through(Slot<D>::ovec(slot, tid, db * 4 + cq), o[db][4 * cq], o[db][4 * cq + 1], o[db][4 * cq + 2],
+                           o[db][4 * cq + 3]);
+      }
+      if (give) {
+        // each thread's stores are in memory when its counter reaches zero; after the barrier all are
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0)
+          __hip_atomic_store(p.flags + span * p.team_size + member, p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       }
     }
   }
@@ -622,7 +737,7 @@ __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParam
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63, j = lane & 31, hf = lane >> 5;
   const int db = int(blockIdx.y);
-  const int n_merge = (p.n_teams - 1) * p.team_size;
+  const int n_merge = p.handoff ? 0 : (p.n_teams - 1) * p.team_size;
   if (int(blockIdx.x) >= n_merge) {                // score of a head no boundary cuts
     const int h = int(blockIdx.x) - n_merge;
     if (db == 0 && tid == 0 && p.n_cut_units[h] == 0) finish_score(p, h);
@@ -657,17 +772,17 @@ __global__ __launch_bounds__(kThreads) void df_attn_merge_kernel(const AttnParam
     const float w_old = (M == m_new) ? 1.f : fast_exp2((M - m_new) * p.c);
     const float w_new = (st.x == m_new) ? 1.f : fast_exp2((st.x - m_new) * p.c);
     M = m_new;
-    Lt = Lt * w_old + st.y * w_new;
-    La = La * w_old + st.z * w_new;
-    Lb = Lb * w_old + st.w * w_new;
+    Lt = fold(Lt, w_old, st.y, w_new);
+    La = fold(La, w_old, st.z, w_new);
+    Lb = fold(Lb, w_old, st.w, w_new);
     if (!SCORE_ONLY) {
 #pragma unroll
       for (int cq = 0; cq < 4; ++cq) {
         const float4 v4 = *reinterpret_cast<const float4 *>(Slot<D>::ovec(const_cast<float *>(slot), tid, db * 4 + cq));
-        o[4 * cq] = o[4 * cq] * w_old + v4.x * w_new;
-        o[4 * cq + 1] = o[4 * cq + 1] * w_old + v4.y * w_new;
-        o[4 * cq + 2] = o[4 * cq + 2] * w_old + v4.z * w_new;
-        o[4 * cq + 3] = o[4 * cq + 3] * w_old + v4.w * w_new;
+        o[4 * cq] = fold(o[4 * cq], w_old, v4.x, w_new);
+        o[4 * cq + 1] = fold(o[4 * cq + 1], w_old, v4.y, w_new);
+        o[4 * cq + 2] = fold(o[4 * cq + 2], w_old, v4.z, w_new);
+        o[4 * cq + 3] = fold(o[4 * cq + 3], w_old, v4.w, w_new);
       }
     }
   }
@@ -697,6 +812,7 @@ constexpr int kMinQTile = 128;   // smallest query tile any kernel variant uses 
 
 // Workspace layout: [score partials: H * ceil(Nq/128) * 4 floats, rounded up to 256 B]
 //                   [unit counters of the merge kernel: 256 B]
+//                   [hand-over flags: one 8-byte word per workgroup]
 //                   [partial-result slots: 2 per workgroup, kNumCU workgroups at most]
 static size_t part_bytes(int H, int Nq) {
   const size_t tiles = (size_t(Nq) + kMinQTile - 1) / kMinQTile;
@@ -707,8 +823,9 @@ static_assert(kMaxHeads * sizeof(int32_t) <= kTicketBytes, "one counter per head
 static size_t slot_bytes(int d) {
   return size_t(d == 128 ? Slot<128>::kFloats : Slot<64>::kFloats) * sizeof(float);
 }
+constexpr size_t kFlagBytes = kNumCU * sizeof(unsigned long long);
 static size_t workspace_bytes(int H, int d, int Nq) {
-  return part_bytes(H, Nq) + kTicketBytes + 2 * size_t(kNumCU) * slot_bytes(d);
+  return part_bytes(H, Nq) + kTicketBytes + kFlagBytes + 2 * size_t(kNumCU) * slot_bytes(d);
 }
 
 // The decomposition of a launch (A4).  Columns = key tiles of all heads, longest head first.  Query tiles
@@ -752,9 +869,9 @@ static df_status plan(AttnParams &p) {
   p.n_groups = (p.n_qtiles + team - 1) / team;
   p.n_teams = int32_t(teams_of(team));
   p.line_len = int64_t(p.n_groups) * total;
-  // units cut by a span boundary (the same walk as the merge kernel's)
+  // units cut by a span boundary (the same walk as the merge kernel's); with hand-over none is left to it
   for (int h = 0; h < p.H; ++h) p.n_cut_units[h] = 0;
-  for (int k = 1; k < p.n_teams; ++k) {
+  for (int k = 1; k < p.n_teams && !p.handoff; ++k) {
     const int64_t cut = span_begin(k, p.line_len, p.n_teams);
     const int grp = int(cut / total);
     const int col = int(cut - int64_t(grp) * total);
@@ -767,23 +884,67 @@ static df_status plan(AttnParams &p) {
   return DF_OK;
 }
 
+// Whether the workgroups of a launch can hand partial results to each other while it runs: every one of
+// them must be on the device at the same time, i.e. the device must have a compute unit for each (one
+// workgroup fills a compute unit's LDS).  DF_ATTN_HANDOVER=0 in the environment selects the two-kernel
+// path regardless (a process whose queues are restricted to a subset of the compute units needs it).
+static bool handover_possible(int n_wg) {
+  const char *e = std::getenv("DF_ATTN_HANDOVER");   // looked at on every call
+  if (e && e[0] == '0') return false;
+  static std::mutex mu;
+  static int cus[64] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    (void)hipGetLastError();
+    return false;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+      (void)hipGetLastError();
+      n = -1;
+    }
+    cus[dev] = n > 0 ? n : -1;
+  }
+  return cus[dev] >= n_wg;
+}
+
+// A flag value that neither stale workspace contents nor an earlier launch hold: a counter run through a
+// 64-bit mixer, never zero.
+static unsigned long long next_epoch() {
+  static std::atomic<unsigned long long> counter{0x9e3779b97f4a7c15ull ^ (unsigned long long)(uintptr_t)&counter};
+  unsigned long long z = counter.fetch_add(0x9e3779b97f4a7c15ull) + 0x9e3779b97f4a7c15ull;
+  z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+  z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+  z ^= z >> 31;
+  return z ? z : 1ull;
+}
+
 template <int D, bool SCORE_ONLY>
 static df_status launch(AttnParams &p, void *workspace, float *score_out, hipStream_t st) {
+  p.handoff = 0;
   if (df_status s = plan(p)) return s;
+  if (p.n_teams > 1 && handover_possible(p.n_teams * p.team_size)) {
+    p.handoff = 1;
+    for (int h = 0; h < p.H; ++h) p.n_cut_units[h] = 0;
+    p.epoch = next_epoch();
+  }
   char *ws = static_cast<char *>(workspace);
   p.part = score_out ? reinterpret_cast<float *>(ws) : nullptr;
   p.tickets = score_out ? reinterpret_cast<int32_t *>(ws + part_bytes(p.H, p.Nq)) : nullptr;
-  p.slots = reinterpret_cast<float *>(ws + part_bytes(p.H, p.Nq) + kTicketBytes);
+  p.flags = reinterpret_cast<unsigned long long *>(ws + part_bytes(p.H, p.Nq) + kTicketBytes);
+  p.slots = reinterpret_cast<float *>(ws + part_bytes(p.H, p.Nq) + kTicketBytes + kFlagBytes);
   p.score = score_out;
   const int n_wg = p.n_teams * p.team_size;
   const int grid = n_wg >= kXcd ? (n_wg + kXcd - 1) / kXcd * kXcd : n_wg;   // XCD-major numbering needs a multiple of 8
   hipLaunchKernelGGL((df_attn_kernel<D, SCORE_ONLY>), dim3(grid), dim3(kThreads), 0, st, p);
   if (df_status s = launch_status()) return s;
-  // second launch: units cut by span boundaries, and the per-head score sums
-  const int n_merge = (p.n_teams - 1) * p.team_size + (score_out ? p.H : 0);
+  // second launch: units cut by span boundaries (unless they were handed over), and the per-head score sums
+  const int n_merge = (p.handoff ? 0 : (p.n_teams - 1) * p.team_size) + (score_out ? p.H : 0);
   if (n_merge > 0) {
-    hipLaunchKernelGGL((df_attn_merge_kernel<D, SCORE_ONLY>), dim3(n_merge, SCORE_ONLY ? 1 : D / 32), dim3(kThreads), 0, st,
-                       p);
+    hipLaunchKernelGGL((df_attn_merge_kernel<D, SCORE_ONLY>), dim3(n_merge, (SCORE_ONLY || p.handoff) ? 1 : D / 32),
+                       dim3(kThreads), 0, st, p);
     if (df_status s = launch_status()) return s;
   }
   return DF_OK;

@@ -151,6 +151,27 @@ def test_config5_long_context_sampled_rows(df):
     _sampled_parity(df, w, 64, seed=5)
 
 
+def test_two_kernel_path_without_hand_over(df, monkeypatch):
+    """DF_ATTN_HANDOVER=0 leaves the units that span boundaries cut to the second kernel instead of handing
+    their partial sums from workgroup to workgroup.  Same pieces, same order of the same arithmetic: the
+    two paths agree to the last bit, and both meet the oracle (multi-tile heads cut once and several times)."""
+    w = wl.small_ragged(31, H=5, d=128, T=300, hist_frames=6,
+                        types=[wl.HEAD_FULL, wl.HEAD_SINK, wl.HEAD_NEIGHBOR, wl.HEAD_DUMMY, wl.HEAD_FULL], planted=[0])
+    plan = df.df_attn_plan(w.Nq, w.Nq, [w.visible_len(h) for h in range(w.H)])
+    assert plan["n_teams"] > 2 and plan["cut_units"] > 0, plan
+    out_a, score_a, lse_a = gu.run_attn(df, w)
+    monkeypatch.setenv("DF_ATTN_HANDOVER", "0")
+    out_b, score_b, lse_b = gu.run_attn(df, w)
+    monkeypatch.delenv("DF_ATTN_HANDOVER")
+    np.testing.assert_array_equal(out_a, out_b)
+    np.testing.assert_array_equal(lse_a, lse_b)
+    np.testing.assert_array_equal(score_a, score_b)
+    ref, mass, rlse = gu.oracle_rows(w)
+    gu.check_out(out_b, ref, w.name)
+    assert np.abs(score_b - mass.mean(axis=1)).max() <= gu.F_ABS
+    assert np.abs(lse_b - rlse).max() <= gu.LSE_ABS
+
+
 def _direct(df, q, kc, vc, kh, vh, off, sl, scale, want_score=True):
     """df_attn_fwd on explicit tensors (queries and current keys may differ in number)."""
     d = gu.dev()

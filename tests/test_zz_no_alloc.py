@@ -48,7 +48,8 @@ def test_static_scratch_matches_workspace_call_twice_in_a_row(df):
 
 def test_static_scratch_rejects_what_does_not_fit(df):
     d = gu.dev()
-    H, Nq = 64, 524161 + 127            # one 128-row tile more than the static scratch holds at 64 heads
+    H, Nq = 64, 261761                  # one query more than the static scratch holds at 64 heads, d = 128
+    assert df.df_attn_workspace_bytes(H, 128, Nq - 1) <= df.DF_STATIC_SCRATCH_BYTES
     assert df.df_attn_workspace_bytes(H, 128, Nq) > df.DF_STATIC_SCRATCH_BYTES
     q = torch.empty(1, H, 128, dtype=torch.bfloat16, device=d)           # never read: the size check comes first
     a = df.df_attn_args()
