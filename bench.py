@@ -41,22 +41,15 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, datasheet
 # What a kernel made of nothing but v_mfma_f32_32x32x16_bf16 sustains on this part (power-limited clock
-# of about 2.0 GHz instead of the 2.4 GHz of the datasheet figure); measured, see the design doc
+# of about 2.0 GHz instead of the 2.4 GHz of the datasheet figure); measured
 SUSTAINED_BF16_TFLOPS = 2100.0
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, datasheet
 MAX_ABS, MEAN_ABS = 2e-2, 2e-3  # parity bar of the bf16 outputs against the fp64 oracle
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
-KERNEL_SOURCES = ["df_attn.hip", "df_attn_phase.inc", "df_cache.hip", "df_internal.h"]
 
 
-def kernel_source_hash() -> str:
-    """Identifies the kernel sources a profile was taken with (the GPU machine has no git history)."""
-    h = hashlib.sha256()
-    for name in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, "paper_2601_20499_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
-    return h.hexdigest()[:16]
+from paper_2601_20499_amd.profile_summary import kernel_source_hash  # noqa: E402
 
 
 def measured_traffic(workload_name: str):

@@ -12,7 +12,8 @@ import os
 from typing import Optional, Sequence
 
 PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(PKG, "libdf_hip.so")
+# DF_HIP_LIBRARY names another build of the same sources (the host-sanitizer build of the tests)
+LIB_PATH = os.environ.get("DF_HIP_LIBRARY") or os.path.join(PKG, "libdf_hip.so")
 
 DF_OK = 0
 (DF_ERR_NULL, DF_ERR_SHAPE, DF_ERR_UNSUPPORTED, DF_ERR_ALIGN, DF_ERR_WORKSPACE, DF_ERR_RANGE,
