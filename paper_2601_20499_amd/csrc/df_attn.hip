@@ -432,39 +432,40 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
       int t, next_event;            // tile under the cursor; first tile at which step/descriptor change
       uint32_t vo;                  // per lane: byte offset of this lane's 16 bytes of the wave's first row group
       uint32_t step, step_g;        // bytes per tile; bytes between the wave's row groups (kWaves rows apart)
-      bool cur;                     // read through the current-chunk descriptor (else the history's)
-      unsigned dst;                 // LDS byte address of the wave's first row group in the tile's buffer
     };
-    auto relocate = [&](Cursor &c) {
+    // the descriptor each cursor currently reads through (the history's or the current chunk's); kept outside
+    // the struct and changed only where a cursor crosses into another region, not selected per tile
+    __amdgpu_buffer_rsrc_t rs_k_now = rs_kh, rs_v_now = rs_vh;
+    auto relocate = [&](Cursor &c, bool is_v) {
       const int t = c.t;
+      bool cur = true;
       if (t >= t_end) {             // absent tile: out of range for every lane, the loads write zeros
         c.vo = kNoTile; c.step = 0; c.step_g = 0; c.next_event = INT32_MAX;
-        c.cur = true;
       } else if (t < nt0 + nt1) {
         const uint32_t row0 = t < nt0 ? uint32_t(t * kKT) : uint32_t(sink + (t - nt0) * kKT);
         c.vo = lane_vo_hist + row0 * L::ROWB; c.step = kKT * L::ROWB; c.step_g = kWaves * L::ROWB;
         c.next_event = min(t < nt0 ? nt0 : nt0 + nt1, t_end);
-        c.cur = false;
+        cur = false;
       } else {
         c.vo = lane_vo_cur + uint32_t((t - nt0 - nt1) * kKT) * cur_stride_b;
         c.step = kKT * cur_stride_b; c.step_g = kWaves * cur_stride_b; c.next_event = t_end;
-        c.cur = true;
       }
+      if (is_v) rs_v_now = cur ? rs_vc : rs_vh;
+      else rs_k_now = cur ? rs_kc : rs_kh;
     };
-    // one tile on: next LDS buffer, next tile's bytes; then this wave's share of that tile goes out
-    auto advance_and_load = [&](Cursor &c, bool is_v) {
+    // one tile on: next tile's bytes; then this wave's share of that tile goes out into LDS buffer `slot`
+    // (a compile-time number: the tile loop is unrolled over the four buffers)
+    auto advance_and_load = [&](Cursor &c, bool is_v, int slot) {
       const unsigned tile_b = is_v ? L::VTILE : L::KTILE, gs = is_v ? L::VGS : L::KGS;
-      const unsigned base = (is_v ? lds_address(lds_v) : lds_address(lds_k)) + wave * gs;
+      const unsigned dst = (is_v ? lds_address(lds_v) : lds_address(lds_k)) + wave * gs + slot * tile_b;
       ++c.t;
       c.vo += c.step;
-      c.dst = (c.dst == base + (kNBuf - 1) * tile_b) ? base : c.dst + tile_b;
-      if (c.t == c.next_event) relocate(c);
+      if (c.t == c.next_event) relocate(c, is_v);
 #pragma unroll
       for (int i = 0; i < GPW; ++i) {
-        lds_void *d = (lds_void *)(uintptr_t)(c.dst + kWaves * i * gs);
+        lds_void *d = (lds_void *)(uintptr_t)(dst + kWaves * i * gs);
         const int vo = int(c.vo + uint32_t(i) * c.step_g);
-        if (c.cur) __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vc : rs_kc, d, 16, vo, 0, 0, 0);
-        else __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_vh : rs_kh, d, 16, vo, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v ? rs_v_now : rs_k_now, d, 16, vo, 0, 0, 0);
       }
     };
 
@@ -512,21 +513,12 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
       for (int ts = 0; ts < 2; ++ts)
 #pragma unroll
         for (int e = 0; e < 8; ++e) pb[kb][ts][e] = (__bf16)0.f;
-    int k_slot = 0, v_slot = kNBuf - 1;      // LDS buffer of K(t) and of V(t-1)
     // the cursors start on the last tiles the prologue has issued (K: t_begin + 2 in buffer 2, V: t_begin + 1 in buffer 1)
     Cursor kc, vc;
     kc.t = t_begin + 2;
-    kc.dst = lds_address(lds_k) + wave * L::KGS + 2 * L::KTILE;
-    relocate(kc);
+    relocate(kc, false);
     vc.t = t_begin + 1;
-    vc.dst = lds_address(lds_v) + wave * L::VGS + 1 * L::VTILE;
-    relocate(vc);
-    // every wave issues the same number of loads once per VALU phase (absent tiles load zeros), so
-    // the s_waitcnt count at the end of the MFMA phase holds
-    auto phase_loads = [&]() {
-      advance_and_load(kc, false);
-      if (!SCORE_ONLY) advance_and_load(vc, true);
-    };
+    relocate(vc, true);
 
     const int seg_end0 = nt0 - 1, seg_end1 = nt0 + nt1 - 1;
     // last tile of the segment that tile t lies in (empty segments have no tiles)
@@ -554,10 +546,16 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
         }
       return (c4[0] + c4[1]) + (c4[2] + c4[3]);
     };
-#pragma unroll 1
-    for (int t = t_begin; t <= t_end; ++t) {
+    // One tile iteration; SLOT = LDS buffer of K(t), a compile-time number (the loop below is unrolled over
+    // the four buffers, so no buffer address is computed at run time).  V(t-1) is in buffer SLOT + 3, the
+    // loads of this iteration fill K(t+3) into buffer SLOT + 3 and V(t+2) into buffer SLOT + 2 (mod 4).
+    int t = t_begin;
+    auto iteration = [&](auto slot_c) {
+      constexpr int SLOT = decltype(slot_c)::value;
       int n_valid_t = kKT;                    // real keys in tile t: only a segment's last tile can be partial
+      bool seg_last = false;                  // tile t ends the sink or the window region (or the unit)
       if (t == next_seg_end) {
+        seg_last = true;
         if (t == seg_end0) n_valid_t = sink - (nt0 - 1) * kKT;
         else if (t == seg_end1) n_valid_t = len_h - sink - (nt1 - 1) * kKT;
         else n_valid_t = p.Nc - (nt2 - 1) * kKT;
@@ -566,26 +564,27 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
       // ================= MFMA phase =================
       // Always both products: at the first tile the second one multiplies P = 0 with the zero-filled
       // spare V buffer, after the last tile the first one computes scores of a stale tile that nobody reads.
-      {
-        const unsigned k_addr = k_lane_addr + k_slot * L::KTILE;
-        const unsigned v_addr = v_lane_addr + v_slot * L::VTILE;
-        if (wave_live) MfmaPhase<D, !SCORE_ONLY>::run(k_addr, v_addr, qf, pb, s, o);
-        k_slot = (k_slot == kNBuf - 1) ? 0 : k_slot + 1;   // slot of K(t+1)
-        v_slot = (v_slot == kNBuf - 1) ? 0 : v_slot + 1;   // slot of V(t)
-      }
+      if (wave_live)
+        MfmaPhase<D, !SCORE_ONLY>::run(k_lane_addr + SLOT * L::KTILE, v_lane_addr + ((SLOT + 3) & 3) * L::VTILE, qf, pb, s, o);
       // One workgroup barrier per iteration, taken by group 1 here and by group 0 after its VALU
       // phase: between two barriers group 0 runs MFMA(t), VALU(t) and group 1 runs VALU(t-1), MFMA(t),
       // so the two waves of a SIMD are in opposite phases without being locked phase by phase.
-      // Before the barrier a wave makes sure that its loads of all but the latest VALU phase have
-      // landed (tiles up to K(t+2), V(t+1)); behind it every wave has finished MFMA(t-1), whose
-      // tiles' buffers the next VALU phases overwrite.
-      auto iteration_barrier = [&]() {
+      // Before a barrier a wave waits for those of its loads that the MFMA phases behind that barrier read.
+      // Tile K(t+3) / V(t+2), issued in VALU phase t, is first read in MFMA phase t+3, which begins behind
+      // barrier t+2 (barrier n = the one group 0 takes after VALU(n) and group 1 after MFMA(n)).  Group 0
+      // issues it before barrier t and may leave the loads of its latest two phases in flight; group 1
+      // issues it behind barrier t and may leave those of its latest phase in flight.  Either way a load has
+      // about two iterations to land.  Behind a barrier every wave has finished MFMA(t-1), whose tiles'
+      // buffers the next VALU phases overwrite.
+      if (group == 1) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDmaPerPhase) : "memory");
         lds_barrier();
-      };
-      if (group == 1) iteration_barrier();
+      }
       // ================= VALU / memory phase =================
-      phase_loads();
+      // every wave issues the same number of loads once per VALU phase (absent tiles load zeros), so
+      // the s_waitcnt counts hold
+      advance_and_load(kc, false, (SLOT + 3) & 3);
+      if (!SCORE_ONLY) advance_and_load(vc, true, (SLOT + 2) & 3);
       if (t < t_end && wave_live) {
         if (n_valid_t < kKT) {                // keys past the end of the segment
           const int key0 = 8 * hf;
@@ -624,12 +623,26 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
           l_new = l + ts;
         }
         l = l_new;
-        if (t == seg_end0 || t == seg_end1) {  // rare: keep the bookkeeping out of the common path
+        if (seg_last) {                       // rare: keep the bookkeeping out of the common path
           if (t == seg_end0) { snap_m0 = m; snap_l0 = l; }
           if (t == seg_end1) { snap_m1 = m; snap_l1 = l; }
         }
       }
-      if (group == 0) iteration_barrier();
+      if (group == 0) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kDmaPerPhase) : "memory");
+        lds_barrier();
+      }
+    };
+#pragma unroll 1
+    for (;;) {
+      iteration(std::integral_constant<int, 0>{});
+      if (++t > t_end) break;
+      iteration(std::integral_constant<int, 1>{});
+      if (++t > t_end) break;
+      iteration(std::integral_constant<int, 2>{});
+      if (++t > t_end) break;
+      iteration(std::integral_constant<int, 3>{});
+      if (++t > t_end) break;
     }
     // no load of this piece may land in the next one's tiles, and no wave may still be reading them
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
