@@ -89,9 +89,9 @@ df_status df_head_context(int32_t head_type, int32_t T, int32_t sink_frames,
  * Launches: one kernel, plus a small second one when score_out is given.  The
  * keys of a (head, query tile) unit may be split between workgroups; when the
  * device has a compute unit for every workgroup of the launch (it has on the
- * part this library is written for) the partial sums travel from workgroup to
- * workgroup through the workspace while the kernel runs, each waiting for the
- * one before it with a bounded wait: should a workgroup never get to run
+ * part this library is written for) the partial sums go through the workspace
+ * while the kernel runs and the workgroup with a unit's last keys collects
+ * them, with a bounded wait: should a workgroup never get to run
  * (compute units taken away from the process), the rows concerned come out as
  * NaN after some seconds instead of hanging the device.  DF_ATTN_HANDOVER=0 in
  * the environment (read at every call) selects the other path, in which a

@@ -13,13 +13,14 @@
 // group: its members walk the same columns at the same time, each for its own
 // 256 queries, so they share every K/V tile in L2 while it is hot, and every
 // team does the same amount of work.  A unit that lies inside one span is
-// finished in place.  A unit cut by span boundaries is summed piece by piece
-// along the chain of workgroups that hold its pieces (same member of
-// consecutive teams): every workgroup walks its span from the END, so the piece
-// that begins a cut unit is the first thing a workgroup does and the piece that
-// completes one is the last, and each link finds the sum of the earlier pieces
-// (m, l, region sums, unnormalised O in fp32) waiting in the workspace, adds its
-// own in key order and either passes the sum on or writes the result.  This
+// finished in place.  A unit cut by span boundaries is put together by the
+// workgroup that holds its last piece (the pieces lie with the same member of
+// consecutive teams): every workgroup walks its span from the END, so a piece
+// that does not end its unit is done early - its sums (m, l, region sums,
+// unnormalised O in fp32) go to the workspace and a flag goes up - and the
+// piece that ends a unit is the last thing a workgroup does: it waits for the
+// flags of the earlier pieces, folds their sums and its own in key order and
+// writes the result.  This
 // needs every workgroup of the launch on the device at once; when the device
 // cannot hold them all, the pieces are left in the workspace and a second kernel
 // puts them together in the same order with the same arithmetic.  Teams are laid
@@ -377,11 +378,11 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     const int t_begin = int(piece_pos - unit_lo);
     const int t_end = int(pos_end - unit_lo);
     pos_end = piece_pos;
-    // Hand-over: a piece that does not begin its unit takes over what the unit's earlier pieces have
-    // summed (always from the same member of the previous team: the pieces of a unit lie in consecutive
-    // spans), a piece that does not end its unit passes the sum on to the same member of the next team.
-    const bool take = p.handoff && t_begin > 0;
+    // Hand-over: a piece that does not end its unit leaves its partial sums in the workspace and raises a
+    // flag; the piece that ends the unit (always the last thing its workgroup does) collects the sums of
+    // all earlier pieces - they lie with the same member of the preceding teams - and finishes the unit.
     const bool give = p.handoff && t_end < n_tiles;
+    const bool take = p.handoff && t_begin > 0 && t_end == n_tiles;
     const int qt = grp * p.team_size + member;     // this workgroup's query tile in this group
     if (qt >= p.n_qtiles) continue;                // the last group may have fewer tiles than the team has members
     const int q0 = qt * kBQ + wave * 32;
@@ -661,45 +662,72 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     const bool valid = row < p.Nq;
     float m_u = m, lt_u = lt, l1_u = l1, l2_u = l2;
     if (take) {
-      // The earlier pieces' sum was written when the other workgroup began its span (or, if the unit covers
-      // that whole span, as soon as it had taken over from the one before it).  Wait until the flag says it
-      // is in memory; the wait is bounded so that a workgroup that never runs cannot hang the device: the
-      // rows then come out as NaN.
-      const int give_span = span - 1;
-      const bool give_at_start = unit_lo <= span_begin(give_span, p.line_len, p.n_teams);
-      const float *slot = p.slots + slot_index(p, give_span, give_at_start ? 0 : 1, member) * Slot<D>::kFloats;
+      // The earlier pieces were written when their workgroups began their spans (a piece that fills a whole
+      // span: when that workgroup ended), i.e. long ago or at about this time.  Wait until every flag says
+      // its piece is in memory; the wait is bounded so that a workgroup that never runs cannot hang the
+      // device: the rows then come out as NaN.
+      int s_first = span - 1;                      // span that holds the unit's first tile
+      while (s_first > 0 && span_begin(s_first, p.line_len, p.n_teams) > unit_lo) --s_first;
       if (tid == 0) {
-        unsigned long long *flag = p.flags + give_span * p.team_size + member;
-        int ok = 0;
-        for (int spin = 0; spin < kSpinLimit && !ok; ++spin) {
-          ok = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == p.epoch;
-          if (!ok) __builtin_amdgcn_s_sleep(16);
+        int all = 1;
+        for (int sp = s_first; sp < span; ++sp) {
+          unsigned long long *flag = p.flags + sp * p.team_size + member;
+          int ok = 0;
+          for (int spin = 0; spin < kSpinLimit && !ok; ++spin) {
+            ok = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == p.epoch;
+            if (!ok) __builtin_amdgcn_s_sleep(16);
+          }
+          // a flag has one reader: put it back, so that a replay of this launch (same epoch) starts clean
+          __hip_atomic_store(flag, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+          all &= ok;
         }
-        // the flag has one reader: put it back, so that a replay of this launch (same epoch) starts clean
-        __hip_atomic_store(flag, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        lds_ok = ok;
+        lds_ok = all;
       }
       __syncthreads();
       const float poison = lds_ok ? 0.f : NAN;
-      const f32x4 st = load4_through(Slot<D>::stats(const_cast<float *>(slot), tid));
-      // earlier pieces first: the same order and arithmetic as the merge kernel
-      const float m_new = fmaxf(st[0], m);
-      const float w_h = (st[0] == m_new) ? 1.f : fast_exp2((st[0] - m_new) * p.c);
+      // earlier pieces first, this one last: the same order and arithmetic as the merge kernel
+      float M = -INFINITY, Lt = 0.f, La = 0.f, Lb = 0.f;
+      f32x16 acc[DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+#pragma unroll 1
+      for (int sp = s_first; sp < span; ++sp) {
+        const int which = unit_lo > span_begin(sp, p.line_len, p.n_teams) ? 1 : 0;
+        const float *slot = p.slots + slot_index(p, sp, which, member) * Slot<D>::kFloats;
+        const f32x4 st = load4_through(Slot<D>::stats(const_cast<float *>(slot), tid));
+        const float m_new = fmaxf(M, st[0]);
+        const float w_old = (M == m_new) ? 1.f : fast_exp2((M - m_new) * p.c);
+        const float w_new = (st[0] == m_new) ? 1.f : fast_exp2((st[0] - m_new) * p.c);
+        M = m_new;
+        Lt = fold(Lt, w_old, st[1], w_new);
+        La = fold(La, w_old, st[2], w_new);
+        Lb = fold(Lb, w_old, st[3], w_new);
+        if (!SCORE_ONLY) {
+#pragma unroll
+          for (int db = 0; db < DB; ++db) {
+            f32x4 v[4];
+            load4x4_through(Slot<D>::ovec(const_cast<float *>(slot), tid, db * 4), kThreads * 4, v);
+#pragma unroll
+            for (int cq = 0; cq < 4; ++cq)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[db][4 * cq + e] = fold(acc[db][4 * cq + e], w_old, v[cq][e], w_new);
+          }
+        }
+      }
+      const float m_new = fmaxf(M, m);
+      const float w_h = (M == m_new) ? 1.f : fast_exp2((M - m_new) * p.c);
       const float w_t = (m == m_new) ? 1.f : fast_exp2((m - m_new) * p.c);
       m_u = m_new + poison;
-      lt_u = fold(st[1], w_h, lt, w_t);
-      l1_u = fold(st[2], w_h, l1, w_t);
-      l2_u = fold(st[3], w_h, l2, w_t);
+      lt_u = fold(Lt, w_h, lt, w_t);
+      l1_u = fold(La, w_h, l1, w_t);
+      l2_u = fold(Lb, w_h, l2, w_t);
       if (!SCORE_ONLY) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          f32x4 v[4];
-          load4x4_through(Slot<D>::ovec(const_cast<float *>(slot), tid, db * 4), kThreads * 4, v);
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int cq = 0; cq < 4; ++cq)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[db][4 * cq + e] = fold(v[cq][e], w_h, o[db][4 * cq + e], w_t);
-        }
+          for (int v = 0; v < 16; ++v) o[db][v] = fold(acc[db][v], w_h, o[db][v], w_t);
       }
       __syncthreads();                             // lds_ok is free again
     }
