@@ -174,6 +174,13 @@ typedef struct df_attn_plan_info {
   int64_t line_len;    /* n_groups * total_cols                                                 */
   int64_t span_min, span_max; /* shortest and longest span, in key tiles                        */
   double busy;         /* share of the 256 workgroup slots that hold a query tile, averaged over the line */
+  /* the walk over all spans that the kernel takes, checked on the host (per member of a team): */
+  int32_t pieces;      /* parts of units that the spans hold                                     */
+  int32_t gives;       /* pieces that do not end their unit (their sums are left for a later span) */
+  int32_t takes;       /* pieces that end a unit begun in an earlier span (they collect those sums) */
+  int32_t max_pieces_per_unit;
+  int32_t consistent;  /* 1 if the pieces tile every span, the pieces of every unit are consecutive, lie
+                          in consecutive spans and cover it, and no span gives or takes more than once  */
 } df_attn_plan_info;
 
 df_status df_attn_plan(int32_t H, int32_t Nq, int32_t Nc, const int32_t *hist_len,

@@ -63,7 +63,9 @@ class df_attn_plan_info(C.Structure):
     _fields_ = [("n_qtiles", C.c_int32), ("team_size", C.c_int32), ("n_groups", C.c_int32), ("n_teams", C.c_int32),
                 ("workgroups", C.c_int32), ("cut_units", C.c_int32),
                 ("total_cols", C.c_int64), ("line_len", C.c_int64), ("span_min", C.c_int64), ("span_max", C.c_int64),
-                ("busy", C.c_double)]
+                ("busy", C.c_double),
+                ("pieces", C.c_int32), ("gives", C.c_int32), ("takes", C.c_int32), ("max_pieces_per_unit", C.c_int32),
+                ("consistent", C.c_int32)]
 
 
 class df_cache(C.Structure):

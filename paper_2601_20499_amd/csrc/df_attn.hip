@@ -79,6 +79,7 @@
 #include <mutex>
 #include <numeric>
 #include <type_traits>
+#include <vector>
 
 #include "df_internal.h"
 
@@ -246,11 +247,34 @@ __host__ __device__ __forceinline__ int64_t span_begin(int64_t s, int64_t line_l
   return (s * line_len) / n_spans;
 }
 
+// One piece of a span: the part of a unit (group of query tiles x head) that the span holds.  The same
+// walk - from the span's end to its start - is taken by the kernel and by the host check of a plan.
+struct Piece {
+  int grp, hh;          // group of query tiles; head (index into the length-sorted order)
+  int n_tiles;          // key tiles of the unit
+  int t_begin, t_end;   // the piece: tiles [t_begin, t_end) of the unit
+  int64_t unit_lo;      // line position of the unit's first tile
+  int64_t pos;          // line position of the piece's first tile
+};
 // Head (index into the length-sorted order) that owns column `col`.
 __host__ __device__ __forceinline__ int head_of_column(const AttnParams &p, int col) {
   int hh = 0;
   while (col >= p.cum[hh + 1]) ++hh;
   return hh;
+}
+
+// The piece of span [span_lo, ...) that ends at line position pos_end (span_lo < pos_end <= the span's end).
+__host__ __device__ __forceinline__ Piece piece_ending_at(const AttnParams &p, int64_t span_lo, int64_t pos_end) {
+  Piece c;
+  c.grp = int((pos_end - 1) / p.total_cols);
+  const int col = int((pos_end - 1) - int64_t(c.grp) * p.total_cols);
+  c.hh = head_of_column(p, col);
+  c.n_tiles = p.cum[c.hh + 1] - p.cum[c.hh];
+  c.unit_lo = int64_t(c.grp) * p.total_cols + p.cum[c.hh];
+  c.pos = span_lo > c.unit_lo ? span_lo : c.unit_lo;
+  c.t_begin = int(c.pos - c.unit_lo);
+  c.t_end = int(pos_end - c.unit_lo);
+  return c;
 }
 
 // Normalise, round and store one thread's share of 32 output columns (block db) of a finished unit.
@@ -362,9 +386,8 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
 #pragma unroll 1
   for (int64_t pos_end = span_hi; pos_end > span_lo;) {
     // ---- the piece that ends at `pos_end`: group of query tiles, head, first and last tile of this team's share
-    const int grp = int((pos_end - 1) / p.total_cols);
-    const int col = int((pos_end - 1) - int64_t(grp) * p.total_cols);
-    const int hh = head_of_column(p, col);         // index into the length-sorted head order
+    const Piece piece = piece_ending_at(p, span_lo, pos_end);
+    const int grp = piece.grp, hh = piece.hh;      // hh: index into the length-sorted head order
     const int h = p.order[hh];
     const int64_t hoff = p.hist_off[h];
     const int len_h = p.hist_len[h];
@@ -372,11 +395,10 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
     const int nt0 = (sink + kKT - 1) / kKT;
     const int nt1 = (len_h - sink + kKT - 1) / kKT;
     const int nt2 = (p.Nc + kKT - 1) / kKT;
-    const int n_tiles = nt0 + nt1 + nt2;
-    const int64_t unit_lo = int64_t(grp) * p.total_cols + p.cum[hh];   // line position of the unit's first tile
-    const int64_t piece_pos = max(span_lo, unit_lo);
-    const int t_begin = int(piece_pos - unit_lo);
-    const int t_end = int(pos_end - unit_lo);
+    const int n_tiles = piece.n_tiles;             // = nt0 + nt1 + nt2
+    const int64_t unit_lo = piece.unit_lo;         // line position of the unit's first tile
+    const int64_t piece_pos = piece.pos;
+    const int t_begin = piece.t_begin, t_end = piece.t_end;
     pos_end = piece_pos;
     // Hand-over: a piece that does not end its unit leaves its partial sums in the workspace and raises a
     // flag; the piece that ends the unit (always the last thing its workgroup does) collects the sums of
@@ -1074,6 +1096,61 @@ extern "C" df_status df_attn_plan(int32_t H, int32_t Nq, int32_t Nc, const int32
     out->span_max = std::max(out->span_max, len);
   }
   out->busy = double(out->workgroups) / kNumCU * double(p.n_qtiles) / double(int64_t(p.n_groups) * p.team_size);
+  // Walk every span the way the kernel does and check what the hand-over relies on: the pieces of a span
+  // tile it, the pieces of a unit are consecutive, lie in consecutive spans and cover the unit, and a span
+  // holds at most one piece that leaves its sums for a later span and at most one that collects earlier ones.
+  out->pieces = out->gives = out->takes = out->max_pieces_per_unit = 0;
+  out->consistent = 1;
+  int64_t expect_unit = -1;        // unit_lo of the unit whose next piece the walk must meet, or -1
+  int expect_t = 0, unit_pieces = 0, first_span = 0;
+  for (int span = 0; span < p.n_teams; ++span) {
+    const int64_t lo = span_begin(span, p.line_len, p.n_teams), hi = span_begin(span + 1, p.line_len, p.n_teams);
+    // the kernel walks from the end; collect, then check in line order
+    std::vector<Piece> list;
+    for (int64_t pos_end = hi; pos_end > lo;) {
+      const Piece c = piece_ending_at(p, lo, pos_end);
+      if (c.pos >= pos_end || c.pos < lo) { out->consistent = 0; break; }
+      list.push_back(c);
+      pos_end = c.pos;
+    }
+    const int n = int(list.size());
+    int gives = 0, takes = 0;
+    int64_t at = lo;
+    for (int i = n - 1; i >= 0; --i) {
+      const Piece &c = list[i];
+      if (c.pos != at || c.t_begin < 0 || c.t_end > c.n_tiles || c.t_begin >= c.t_end) out->consistent = 0;
+      at = c.pos + (c.t_end - c.t_begin);
+      if (c.t_begin == 0) {
+        if (expect_unit != -1) out->consistent = 0;          // the unit before was left unfinished
+        unit_pieces = 0;
+        first_span = span;
+      } else if (expect_unit != c.unit_lo || expect_t != c.t_begin || i != n - 1) {
+        out->consistent = 0;                                  // a continued unit is the first piece of its span
+      }
+      ++unit_pieces;
+      if (c.t_end < c.n_tiles) {
+        ++gives;
+        expect_unit = c.unit_lo;
+        expect_t = c.t_end;
+        if (i != 0) out->consistent = 0;                      // an unfinished unit is the last piece of its span
+      } else {
+        expect_unit = -1;
+        if (c.t_begin > 0) {
+          ++takes;
+          // the kernel finds the span of the unit's first piece by stepping back from its own
+          int s_first = span - 1;
+          while (s_first > 0 && span_begin(s_first, p.line_len, p.n_teams) > c.unit_lo) --s_first;
+          if (s_first != first_span || unit_pieces != span - first_span + 1) out->consistent = 0;
+        }
+        out->max_pieces_per_unit = std::max(out->max_pieces_per_unit, unit_pieces);
+      }
+    }
+    if (at != hi || gives > 1 || takes > 1) out->consistent = 0;
+    out->pieces += n;
+    out->gives += gives;
+    out->takes += takes;
+  }
+  if (expect_unit != -1) out->consistent = 0;
   return DF_OK;
 }
 

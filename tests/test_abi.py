@@ -3,6 +3,7 @@ ctypes mirror of the argument structs matches the C layout, host-only entry poin
 the oracle, and argument validation returns the documented codes without touching a GPU."""
 import ctypes as C
 import os
+import random
 import re
 import subprocess
 import sys
@@ -255,6 +256,23 @@ def test_attention_plan_fills_the_machine(b, Nq, mix):
     cols = sum(tiles(s) + tiles(l - s) + tiles(Nq) for l, s in zip(hist_len, sink_len))
     assert r["total_cols"] == cols and r["line_len"] == cols * r["n_groups"]
     assert 0 <= r["cut_units"] <= (r["n_teams"] - 1) * r["team_size"]
+    # the walk over the spans that the kernel takes: what the hand-over between workgroups relies on
+    assert r["consistent"] == 1, r
+    assert r["takes"] <= min(r["gives"], r["n_teams"] - 1) and r["gives"] <= r["n_teams"] - 1
+    assert (r["gives"] == 0) == (r["takes"] == 0) == (r["cut_units"] == 0)
+    # the same counts from the plan's definition: columns = key tiles of the heads, longest head first, once per
+    # group of query tiles; boundaries at k * line_len / n_teams; a boundary strictly inside a unit cuts it
+    per_head = sorted((tiles(s) + tiles(l - s) + tiles(Nq) for l, s in zip(hist_len, sink_len)), reverse=True)
+    starts, at = [], 0
+    for _ in range(r["n_groups"]):
+        for n in per_head:
+            starts.append((at, at + n))
+            at += n
+    cuts = [k * r["line_len"] // r["n_teams"] for k in range(1, r["n_teams"])]
+    inside = [(lo, hi) for c in cuts for lo, hi in starts if lo < c < hi]
+    assert r["gives"] == len(inside) and r["takes"] == len(set(inside))
+    assert r["pieces"] == len(starts) + len(inside)
+    assert r["max_pieces_per_unit"] == 1 + max([inside.count(u) for u in set(inside)], default=0)
 
 
 def test_attention_plan_small_and_error_cases(b):
@@ -270,3 +288,21 @@ def test_attention_plan_small_and_error_cases(b):
     with pytest.raises(b.DfError) as e:
         b.df_attn_plan(4, 4, [10], [11])                                    # sink longer than the history
     assert e.value.status == b.DF_ERR_RANGE
+
+
+
+def test_attention_plan_piece_walk_is_consistent_for_random_shapes(b):
+    """Seeded random head mixes and query counts (64 heads down to one, empty to long histories, one query to
+    many more query tiles than compute units): the pieces tile every span, every unit's pieces lie in consecutive
+    spans and cover it, and no span leaves or collects partial sums more than once."""
+    rng = random.Random(20499)
+    for _ in range(400):
+        H = rng.choice([1, 2, 3, 5, 12, 40, 64])
+        Nq = rng.choice([1, 63, 64, 255, 256, 257, 1000, 4680, 10800, 24480, 70000])
+        Nc = rng.choice([1, 64, 65, Nq])
+        lens = [rng.choice([0, 0, 1, 63, 64, 65, 500, 1560, 9360, 40000]) for _ in range(H)]
+        sinks = [rng.randint(0, n) for n in lens]
+        r = b.df_attn_plan(Nq, Nc, lens, sinks)
+        assert r["consistent"] == 1, (H, Nq, Nc, lens, r)
+        assert r["workgroups"] <= 256 and r["span_max"] - r["span_min"] <= 1
+        assert r["max_pieces_per_unit"] >= 1 and r["pieces"] >= r["n_teams"]
