@@ -230,6 +230,83 @@ __device__ __forceinline__ f32x4 load4_through(const float *ptr) {
   return v;
 }
 
+// A whole slot (the thread's statistics and its N = D/8 vectors of O) with every load in flight at once and one
+// wait: the slot's address is uniform, the thread's part of it is tid * 16 bytes, vectors are 8 KB apart.
+template <int N>
+__device__ __forceinline__ void load_slot_through(const float *slot, int tid, f32x4 &st, f32x4 (&v)[N]);
+template <>
+__device__ __forceinline__ void load_slot_through<16>(const float *slot, int tid, f32x4 &st, f32x4 (&v)[16]) {
+  static_assert(Slot<128>::kStats * 4 == 0x2000 && kThreads * 16 == 0x2000, "offsets of the asm below");
+  const unsigned vo = unsigned(tid) * 16u;
+  unsigned t0, t1;
+  asm volatile(
+      "global_load_dwordx4 %[st], %[vo], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0x2000, %[vo]\n\t"
+      "global_load_dwordx4 %[v0], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0x4000, %[vo]\n\t"
+      "global_load_dwordx4 %[v1], %[t1], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0x6000, %[vo]\n\t"
+      "global_load_dwordx4 %[v2], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0x8000, %[vo]\n\t"
+      "global_load_dwordx4 %[v3], %[t1], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0xa000, %[vo]\n\t"
+      "global_load_dwordx4 %[v4], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0xc000, %[vo]\n\t"
+      "global_load_dwordx4 %[v5], %[t1], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0xe000, %[vo]\n\t"
+      "global_load_dwordx4 %[v6], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0x10000, %[vo]\n\t"
+      "global_load_dwordx4 %[v7], %[t1], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0x12000, %[vo]\n\t"
+      "global_load_dwordx4 %[v8], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0x14000, %[vo]\n\t"
+      "global_load_dwordx4 %[v9], %[t1], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0x16000, %[vo]\n\t"
+      "global_load_dwordx4 %[v10], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0x18000, %[vo]\n\t"
+      "global_load_dwordx4 %[v11], %[t1], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0x1a000, %[vo]\n\t"
+      "global_load_dwordx4 %[v12], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0x1c000, %[vo]\n\t"
+      "global_load_dwordx4 %[v13], %[t1], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0x1e000, %[vo]\n\t"
+      "global_load_dwordx4 %[v14], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0x20000, %[vo]\n\t"
+      "global_load_dwordx4 %[v15], %[t1], %[sb] sc0 sc1\n\t"
+      "s_waitcnt vmcnt(0)"
+      : [st] "=&v"(st), [v0] "=&v"(v[0]), [v1] "=&v"(v[1]), [v2] "=&v"(v[2]), [v3] "=&v"(v[3]), [v4] "=&v"(v[4]), [v5] "=&v"(v[5]), [v6] "=&v"(v[6]), [v7] "=&v"(v[7]), [v8] "=&v"(v[8]), [v9] "=&v"(v[9]), [v10] "=&v"(v[10]), [v11] "=&v"(v[11]), [v12] "=&v"(v[12]), [v13] "=&v"(v[13]), [v14] "=&v"(v[14]), [v15] "=&v"(v[15]), [t0] "=&v"(t0), [t1] "=&v"(t1)
+      : [vo] "v"(vo), [sb] "s"(slot)
+      : "memory");
+}
+template <>
+__device__ __forceinline__ void load_slot_through<8>(const float *slot, int tid, f32x4 &st, f32x4 (&v)[8]) {
+  static_assert(Slot<64>::kStats * 4 == 0x2000 && kThreads * 16 == 0x2000, "offsets of the asm below");
+  const unsigned vo = unsigned(tid) * 16u;
+  unsigned t0, t1;
+  asm volatile(
+      "global_load_dwordx4 %[st], %[vo], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0x2000, %[vo]\n\t"
+      "global_load_dwordx4 %[v0], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0x4000, %[vo]\n\t"
+      "global_load_dwordx4 %[v1], %[t1], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0x6000, %[vo]\n\t"
+      "global_load_dwordx4 %[v2], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0x8000, %[vo]\n\t"
+      "global_load_dwordx4 %[v3], %[t1], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0xa000, %[vo]\n\t"
+      "global_load_dwordx4 %[v4], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0xc000, %[vo]\n\t"
+      "global_load_dwordx4 %[v5], %[t1], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t0], 0xe000, %[vo]\n\t"
+      "global_load_dwordx4 %[v6], %[t0], %[sb] sc0 sc1\n\t"
+      "v_add_u32 %[t1], 0x10000, %[vo]\n\t"
+      "global_load_dwordx4 %[v7], %[t1], %[sb] sc0 sc1\n\t"
+      "s_waitcnt vmcnt(0)"
+      : [st] "=&v"(st), [v0] "=&v"(v[0]), [v1] "=&v"(v[1]), [v2] "=&v"(v[2]), [v3] "=&v"(v[3]), [v4] "=&v"(v[4]), [v5] "=&v"(v[5]), [v6] "=&v"(v[6]), [v7] "=&v"(v[7]), [t0] "=&v"(t0), [t1] "=&v"(t1)
+      : [vo] "v"(vo), [sb] "s"(slot)
+      : "memory");
+}
+
 // Weighted sum of the earlier pieces' value and a later piece's, written out so that both places that
 // put pieces together (in the main kernel and in the merge kernel) round in the same way.
 __device__ __forceinline__ float fold(float earlier, float w_earlier, float later, float w_later) {
@@ -708,48 +785,73 @@ __global__ __launch_bounds__(kThreads) void df_attn_kernel(const AttnParams p) {
       __syncthreads();
       const float poison = lds_ok ? 0.f : NAN;
       // earlier pieces first, this one last: the same order and arithmetic as the merge kernel
-      float M = -INFINITY, Lt = 0.f, La = 0.f, Lb = 0.f;
-      f32x16 acc[DB];
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
-#pragma unroll 1
-      for (int sp = s_first; sp < span; ++sp) {
-        const int which = unit_lo > span_begin(sp, p.line_len, p.n_teams) ? 1 : 0;
-        const float *slot = p.slots + slot_index(p, sp, which, member) * Slot<D>::kFloats;
-        const f32x4 st = load4_through(Slot<D>::stats(const_cast<float *>(slot), tid));
-        const float m_new = fmaxf(M, st[0]);
-        const float w_old = (M == m_new) ? 1.f : fast_exp2((M - m_new) * p.c);
-        const float w_new = (st[0] == m_new) ? 1.f : fast_exp2((st[0] - m_new) * p.c);
-        M = m_new;
-        Lt = fold(Lt, w_old, st[1], w_new);
-        La = fold(La, w_old, st[2], w_new);
-        Lb = fold(Lb, w_old, st[3], w_new);
+      if (s_first == span - 1) {
+        // the common case, one earlier piece: all of it is loaded with one wait (folding it into an empty sum
+        // would give back the same numbers)
+        const int which = unit_lo > span_begin(s_first, p.line_len, p.n_teams) ? 1 : 0;
+        const float *slot = p.slots + slot_index(p, s_first, which, member) * Slot<D>::kFloats;
+        f32x4 st, v[D / 8];
+        if constexpr (SCORE_ONLY) st = load4_through(Slot<D>::stats(const_cast<float *>(slot), tid));
+        else load_slot_through<D / 8>(slot, tid, st, v);
+        const float m_new = fmaxf(st[0], m);
+        const float w_h = (st[0] == m_new) ? 1.f : fast_exp2((st[0] - m_new) * p.c);
+        const float w_t = (m == m_new) ? 1.f : fast_exp2((m - m_new) * p.c);
+        m_u = m_new + poison;
+        lt_u = fold(st[1], w_h, lt, w_t);
+        l1_u = fold(st[2], w_h, l1, w_t);
+        l2_u = fold(st[3], w_h, l2, w_t);
         if (!SCORE_ONLY) {
 #pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            f32x4 v[4];
-            load4x4_through(Slot<D>::ovec(const_cast<float *>(slot), tid, db * 4), kThreads * 4, v);
+          for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int cq = 0; cq < 4; ++cq)
 #pragma unroll
-              for (int e = 0; e < 4; ++e) acc[db][4 * cq + e] = fold(acc[db][4 * cq + e], w_old, v[cq][e], w_new);
-          }
+              for (int e = 0; e < 4; ++e) o[db][4 * cq + e] = fold(v[db * 4 + cq][e], w_h, o[db][4 * cq + e], w_t);
         }
-      }
-      const float m_new = fmaxf(M, m);
-      const float w_h = (M == m_new) ? 1.f : fast_exp2((M - m_new) * p.c);
-      const float w_t = (m == m_new) ? 1.f : fast_exp2((m - m_new) * p.c);
-      m_u = m_new + poison;
-      lt_u = fold(Lt, w_h, lt, w_t);
-      l1_u = fold(La, w_h, l1, w_t);
-      l2_u = fold(Lb, w_h, l2, w_t);
-      if (!SCORE_ONLY) {
+      } else {
+        float M = -INFINITY, Lt = 0.f, La = 0.f, Lb = 0.f;
+        f32x16 acc[DB];
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) o[db][v] = fold(acc[db][v], w_h, o[db][v], w_t);
+          for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+#pragma unroll 1
+        for (int sp = s_first; sp < span; ++sp) {
+          const int which = unit_lo > span_begin(sp, p.line_len, p.n_teams) ? 1 : 0;
+          const float *slot = p.slots + slot_index(p, sp, which, member) * Slot<D>::kFloats;
+          const f32x4 st = load4_through(Slot<D>::stats(const_cast<float *>(slot), tid));
+          const float m_new = fmaxf(M, st[0]);
+          const float w_old = (M == m_new) ? 1.f : fast_exp2((M - m_new) * p.c);
+          const float w_new = (st[0] == m_new) ? 1.f : fast_exp2((st[0] - m_new) * p.c);
+          M = m_new;
+          Lt = fold(Lt, w_old, st[1], w_new);
+          La = fold(La, w_old, st[2], w_new);
+          Lb = fold(Lb, w_old, st[3], w_new);
+          if (!SCORE_ONLY) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+              f32x4 v[4];
+              load4x4_through(Slot<D>::ovec(const_cast<float *>(slot), tid, db * 4), kThreads * 4, v);
+#pragma unroll
+              for (int cq = 0; cq < 4; ++cq)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[db][4 * cq + e] = fold(acc[db][4 * cq + e], w_old, v[cq][e], w_new);
+            }
+          }
+        }
+        const float m_new = fmaxf(M, m);
+        const float w_h = (M == m_new) ? 1.f : fast_exp2((M - m_new) * p.c);
+        const float w_t = (m == m_new) ? 1.f : fast_exp2((m - m_new) * p.c);
+        m_u = m_new + poison;
+        lt_u = fold(Lt, w_h, lt, w_t);
+        l1_u = fold(La, w_h, l1, w_t);
+        l2_u = fold(Lb, w_h, l2, w_t);
+        if (!SCORE_ONLY) {
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] = fold(acc[db][v], w_h, o[db][v], w_t);
+        }
       }
       __syncthreads();                             // lds_ok is free again
     }
