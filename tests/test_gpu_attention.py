@@ -232,3 +232,60 @@ def test_sixty_four_heads_and_a_single_query(df):
         q65 = mk(1, 65, d)
         _direct(df, q65, q65, q65, k_p, v_p, off + [off[-1]], sinks + [0], d ** -0.5)
     assert e.value.status == df.DF_ERR_UNSUPPORTED
+
+
+def _random_case(rng):
+    """A seeded random head mix: any number of heads, empty to multi-tile histories with any sink split, query
+    and current-key counts that are multiples of nothing, either head dimension."""
+    H = int(rng.choice([1, 2, 3, 5, 8, 12]))
+    d = int(rng.choice([64, 128]))
+    Nq = int(rng.choice([1, 31, 257, 700, 1283, 2049]))
+    Nc = int(rng.choice([1, 63, 65, 300, Nq]))
+    lens = [int(rng.choice([0, 0, 1, 64, 65, 130, 777, 2500])) for _ in range(H)]
+    sinks = [int(rng.integers(0, n + 1)) for n in lens]
+    return H, d, Nq, Nc, lens, sinks
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_against_the_oracle(df, seed):
+    rng = np.random.default_rng(3000 + seed)
+    H, d, Nq, Nc, lens, sinks = _random_case(rng)
+    g = torch.Generator().manual_seed(3000 + seed)
+    mk = lambda *s: torch.randn(*s, generator=g).to(torch.bfloat16)
+    q, kc, vc = mk(Nq, H, d) + 0.25, mk(Nc, H, d), mk(Nc, H, d)
+    q = q.to(torch.bfloat16)
+    kh = [mk(n, d) for n in lens]
+    vh = [mk(n, d) for n in lens]
+    off = [0]
+    for n in lens:
+        off.append(off[-1] + n)
+    k_p = torch.cat(kh) if off[-1] else torch.zeros(0, d, dtype=torch.bfloat16)
+    v_p = torch.cat(vh) if off[-1] else torch.zeros(0, d, dtype=torch.bfloat16)
+    print(f"seed {seed}: H={H} d={d} Nq={Nq} Nc={Nc} lens={lens} sinks={sinks} plan={df.df_attn_plan(Nq, Nc, lens, sinks)}",
+          flush=True)
+    out, score = _direct(df, q, kc, vc, k_p, v_p, off, sinks, d ** -0.5)
+    # the packed rows of a head are its sink rows followed by its window rows: the oracle sees them as a history
+    # of exactly that length with n_sink sink keys and the rest as window
+    ref, mass, _ = _oracle_direct(q, kc, vc, kh, vh, sinks, [n - s for n, s in zip(lens, sinks)], d ** -0.5)
+    gu.check_out(out, ref, f"random shape {seed}")
+    np.testing.assert_allclose(score, mass.mean(axis=1), atol=gu.F_ABS)
+
+
+def test_query_tiles_in_several_groups_with_cut_units(df):
+    """43 query tiles on 256 workgroup slots run as teams of 15 in 3 groups; with short histories of unequal
+    length the spans cut units in every group.  Every row against the oracle."""
+    g = torch.Generator().manual_seed(43)
+    H, d, Nq, Nc = 4, 64, 256 * 42 + 100, 200
+    lens, sinks = [2000, 900, 0, 1300], [64, 0, 0, 1300]
+    plan = df.df_attn_plan(Nq, Nc, lens, sinks)
+    assert plan["n_groups"] > 1 and plan["takes"] > 0 and plan["consistent"] == 1, plan
+    mk = lambda *s: torch.randn(*s, generator=g).to(torch.bfloat16)
+    q, kc, vc = mk(Nq, H, d), mk(Nc, H, d), mk(Nc, H, d)
+    kh, vh = [mk(n, d) for n in lens], [mk(n, d) for n in lens]
+    off = [0]
+    for n in lens:
+        off.append(off[-1] + n)
+    out, score = _direct(df, q, kc, vc, torch.cat(kh), torch.cat(vh), off, sinks, d ** -0.5)
+    ref, mass, _ = _oracle_direct(q, kc, vc, kh, vh, sinks, [n - s for n, s in zip(lens, sinks)], d ** -0.5)
+    gu.check_out(out, ref, "43 query tiles in 3 groups")
+    np.testing.assert_allclose(score, mass.mean(axis=1), atol=gu.F_ABS)
