@@ -120,3 +120,41 @@ def test_config3_all_thirty_layers_and_the_global_classification(df):
     print(f"per-layer margins min {min(margins):.3e}; global n=360 N=90 margin {g_margin:.3e}; "
           f"dummy heads per layer (global run) {per_layer.tolist()}", flush=True)
     assert per_layer.sum() == 90
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_scores_on_random_shapes(df, seed):
+    """Seeded random head mixes, query counts, sample strides and offsets: scores to 1e-4 against the oracle."""
+    rng = np.random.default_rng(4000 + seed)
+    H = int(rng.choice([1, 3, 6, 12]))
+    dd = int(rng.choice([64, 128]))
+    Nq = int(rng.choice([5, 300, 1283, 3000]))
+    Nc = int(rng.choice([1, 65, 300]))
+    lens = [int(rng.choice([0, 1, 64, 130, 777, 2500])) for _ in range(H)]
+    sinks = [int(rng.integers(0, n + 1)) for n in lens]
+    stride = int(rng.choice([1, 2, 4, 7]))
+    offset = int(rng.integers(0, min(stride, Nq)))
+    g = torch.Generator().manual_seed(4000 + seed)
+    mk = lambda *s: torch.randn(*s, generator=g).to(torch.bfloat16)
+    q, kc = (mk(Nq, H, dd) + 0.25).to(torch.bfloat16), mk(Nc, H, dd)
+    kh = [mk(n, dd) for n in lens]
+    off = [0]
+    for n in lens:
+        off.append(off[-1] + n)
+    k_p = torch.cat(kh) if off[-1] else torch.zeros(0, dd, dtype=torch.bfloat16)
+    d = gu.dev()
+    F = torch.full((H, 3), float("nan"), dtype=torch.float32, device=d)
+    ws = torch.empty(df.df_attn_workspace_bytes(H, dd, Nq), dtype=torch.uint8, device=d)
+    print(f"seed {seed}: H={H} d={dd} Nq={Nq} Nc={Nc} lens={lens} sinks={sinks} stride={stride} offset={offset}", flush=True)
+    df.df_head_score(q.to(d), kc.to(d), k_p.to(d), off, sinks, F, dd ** -0.5,
+                     q_sample_stride=stride, q_offset=offset, workspace=ws)
+    torch.cuda.synchronize()
+    b = lambda t: t.double().numpy()
+    rows = np.arange(offset, Nq, stride)
+    zero_v = [np.zeros((n, dd)) for n in lens]
+    _, mass, _ = orc.layer_attention(b(q), [b(x) for x in kh], zero_v, b(kc), np.zeros((Nc, H, dd)),
+                                     sinks, [n - s for n, s in zip(lens, sinks)], dd ** -0.5, rows=rows)
+    R = mass.mean(axis=1)
+    got = F.cpu().numpy()
+    assert np.abs(got - R).max() <= gu.F_ABS, (got, R)
+    assert np.abs(got.sum(1) - 1).max() <= 1e-5
