@@ -169,7 +169,8 @@ typedef struct df_attn_plan_info {
   int32_t n_groups;    /* ceil(n_qtiles / team_size)                                            */
   int32_t n_teams;     /* spans of the line                                                     */
   int32_t workgroups;  /* n_teams * team_size, at most 256                                      */
-  int32_t cut_units;   /* (head, query tile) units split by a span boundary (merged by a second kernel) */
+  int32_t cut_units;   /* (head, query tile) units split by a span boundary (put together by the last
+                          piece's workgroup, or by a second kernel on the two-kernel path)      */
   int64_t total_cols;  /* key tiles of all heads                                                */
   int64_t line_len;    /* n_groups * total_cols                                                 */
   int64_t span_min, span_max; /* shortest and longest span, in key tiles                        */
